@@ -1,0 +1,59 @@
+"""Builds and wraps the discrete-event simulator under tests/des/ (host only)."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "des")
+_SRC = os.path.join(_DIR, "des_sim.cpp")
+_LIB = os.path.join(_DIR, "libdes_sim.so")
+_lib = None
+
+
+def build(force=False):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.run(["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
+                        "-o", _LIB, _SRC], check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.des_run.restype = ctypes.c_int
+    return _lib
+
+
+def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon):
+    """tasks: list of dicts with core, prio, T, D, c (eta+1 ints), gm, ge (eta ints each).
+    Returns (rc, max_resp[n], jobs_done[n])."""
+    n = len(tasks)
+    max_eta = max(len(t["ge"]) for t in tasks)
+    c = np.zeros((n, max_eta + 1), np.int32)
+    gm = np.zeros((n, max(max_eta, 1)), np.int32)
+    ge = np.zeros((n, max(max_eta, 1)), np.int32)
+    eta = np.zeros(n, np.int32)
+    for i, t in enumerate(tasks):
+        e = len(t["ge"])
+        assert len(t["gm"]) == e and len(t["c"]) == e + 1
+        eta[i] = e
+        c[i, : e + 1] = t["c"]
+        gm[i, :e] = t["gm"]
+        ge[i, :e] = t["ge"]
+    if max_eta == 0:
+        gm = np.zeros((n, 0), np.int32)
+        ge = np.zeros((n, 0), np.int32)
+    gm = np.ascontiguousarray(gm[:, :max_eta])
+    ge = np.ascontiguousarray(ge[:, :max_eta])
+    arr = lambda key: np.ascontiguousarray([t[key] for t in tasks], dtype=np.int32)
+    core, prio, T, D = arr("core"), arr("prio"), arr("T"), arr("D")
+    off = np.ascontiguousarray(offsets, dtype=np.int32)
+    mr = np.zeros(n, np.int32)
+    jd = np.zeros(n, np.int32)
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().des_run(n, max_eta, policy, wait_mode, theta, eps, L, p(core), p(prio), p(T), p(D),
+                         p(off), p(eta), p(c), p(gm), p(ge), horizon, p(mr), p(jd))
+    return rc, mr, jd

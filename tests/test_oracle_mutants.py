@@ -1,0 +1,101 @@
+"""Are the pins sharp?  Each case below plants one plausible mistake in a COPY of the oracle's
+source (a dropped term, a missing jitter, a wrong count, a wrong overhead), builds it with g++
+on the CPU and requires that at least one pin (hand-worked values, closed forms, the textbook
+special case, the simulator) rejects it.  Nothing here touches the GPU library."""
+import os
+import subprocess
+import types
+
+import pytest
+
+import test_oracle_des as des_tests
+import test_oracle_pins as pin_tests
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rta_oracle.cpp")
+
+MUTANTS = {
+    "lemma10_same_core_sum_dropped": (
+        "bool first_sum = tau[i].gpu() || !(options & ORACLE_OPT_LITERAL_LEMMA10);", "bool first_sum = false;"),
+    "jitter_Jg_dropped": ("i64 Jg(const Task &h) const { return h.R - h.Ge; }",
+                          "i64 Jg(const Task &h) const { (void)h; return 0; }"),
+    "jitter_Jc_dropped": ("i64 Jc(const Task &h) const { return h.R - (h.C + h.Gm); }",
+                          "i64 Jc(const Task &h) const { (void)h; return 0; }"),
+    "lemma4_tau_h_not_counted": ("    i64 nu = 1;", "    i64 nu = 0;"),
+    "lemma8_blocking_dropped": ("b = add(b, mul(t.eta + 1, p.eps));", "b = add(b, 0);"),
+    "lemma8_blocking_eta_only": ("b = add(b, mul(t.eta + 1, p.eps));", "b = add(b, mul(t.eta, p.eps));"),
+    "own_runlist_updates_dropped": ("b = add(b, mul(2 * p.eps, t.eta));", "b = add(b, 0);"),
+    "Ge_star_without_updates": ("i64 Ge_star(const Task &t) const { return add(t.Ge, mul(2 * p.eps, t.eta)); }",
+                                "i64 Ge_star(const Task &t) const { return t.Ge; }"),
+    "Gm_star_without_updates": ("i64 Gm_star(const Task &t) const { return add(t.Gm, mul(2 * p.eps, t.eta)); }",
+                                "i64 Gm_star(const Task &t) const { return t.Gm; }"),
+    "lemma1_counts_one_tsg_less": ("i64 nu = n_gpu_tasks() - (t.gpu() ? 1 : 0);",
+                                   "i64 nu = n_gpu_tasks() - 1 - (t.gpu() ? 1 : 0); if (nu < 0) nu = 0;"),
+    "lemma13_same_core_sum_dropped": (
+        "if (same_core(h, i) && tau[h].gpu()) s = add(s, term(R + Jg(tau[h]), tau[h].T, tau[h].Ge));",
+        "if (false) s = 0;"),
+    "eq3_theta_dropped": ("return mul(mul(p.L + p.theta, nu), ceil_div(ge, p.L));",
+                          "return mul(mul(p.L, nu), ceil_div(ge, p.L));"),
+    "eq3_floor_instead_of_ceil": ("return mul(mul(p.L + p.theta, nu), ceil_div(ge, p.L));",
+                                  "return mul(mul(p.L + p.theta, nu), ge / p.L);"),
+    "ceil_is_floor": ("i64 ceil_div(i64 a, i64 b) { return (a + b - 1) / b; }",
+                      "i64 ceil_div(i64 a, i64 b) { return a / b; }"),
+    "hpp_taken_as_other_cores": ("bool same_core(size_t h, size_t i) const { return tau[h].core == tau[i].core; }",
+                                 "bool same_core(size_t h, size_t i) const { return tau[h].core != tau[i].core; }"),
+    "priority_order_reversed": ("return prio[a] > prio[b]; });", "return prio[a] < prio[b]; });"),
+    "G_i_without_Gm": ("t.G = t.Gm + t.Ge;", "t.G = t.Ge;"),
+    "stops_one_iteration_early": ("      } else if (next == R) {\n        break;",
+                                  "      } else if (next == R || true) {\n        break;"),
+}
+
+PINS = [
+    lambda o: [pin_tests.test_classic_hand_examples(o, [1, 2, 3], [4, 6, 13], [1, 3, 10], p, w)
+               for p, w in pin_tests.VARIANTS],
+    lambda o: [pin_tests.test_cpu_only_reduces_to_textbook_rta(o, p, w) for p, w in pin_tests.VARIANTS],
+    pin_tests.test_single_core_gcaps_busy_is_classic_rta_on_inflated_wcet,
+    pin_tests.test_round_robin_interleave_closed_form,
+    pin_tests.test_gcaps_top_task_closed_form,
+    pin_tests.test_table2_printed_verdict,
+    pin_tests.test_table2_hand_worked_values,
+    lambda o: [pin_tests.test_three_task_example(o, p, w, want) for p, w, want in
+               [(2, 1, [26, 26, 73]), (2, 0, [26, 50, 73]), (1, 1, [26, 35, 63]), (1, 0, [26, 43, 63])]],
+    pin_tests.test_carry_in_jitter_other_core,
+    pin_tests.test_self_suspension_jitter_same_core,
+    pin_tests.test_theta_slice_identity,
+    des_tests.test_directed_carry_in_other_core,
+    des_tests.test_directed_self_suspension_same_core,
+    lambda o: [des_tests.test_simulated_response_never_exceeds_bound(o, p, w) for p, w in pin_tests.VARIANTS],
+]
+
+
+def mutant_module(oracle, lib):
+    m = types.SimpleNamespace(**{k: getattr(oracle, k) for k in dir(oracle) if k.isupper()})
+    m.OracleError = oracle.OracleError
+    m.rta_taskset = lambda *a, **kw: oracle.rta_taskset(*a, lib=lib, **kw)
+    return m
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_mutant_is_rejected_by_some_pin(oracle, tmp_path, name):
+    old, new = MUTANTS[name]
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"mutation site for {name} not found exactly once"
+    cpp = tmp_path / "mutant.cpp"
+    cpp.write_text(src.replace(old, new))
+    so = tmp_path / "libmutant.so"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-fPIC", "-shared", "-pthread", "-I", os.path.dirname(SRC),
+                    "-o", str(so), str(cpp)], check=True)
+    m = mutant_module(oracle, oracle.open_library(str(so)))
+    killed_by = None
+    for k, pin in enumerate(PINS):
+        try:
+            pin(m)
+        except AssertionError:
+            killed_by = k
+            break
+    assert killed_by is not None, f"no pin notices the planted mistake '{name}'"
+
+
+def test_unmutated_oracle_passes_the_same_pins(oracle):
+    for pin in PINS:
+        pin(oracle)
