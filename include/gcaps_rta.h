@@ -1,0 +1,150 @@
+/*
+ * gcaps_rta — batched schedulability testing of real-time tasksets on one
+ * AMD Instinct MI355X (gfx950), C ABI.
+ *
+ * For every taskset of a batch the library computes the worst-case
+ * response-time bound R_i of every task (Eq. 1: R_i = C_i + G_i + I^C_i + I^G_i)
+ * under
+ *   - GCAPS preemptive priority-based GPU context scheduling (Sec. 5.3,
+ *     Lemmas 8-15), and/or
+ *   - the default round-robin time-sliced TSG scheduling of the driver
+ *     (Sec. 5.2, Eq. 3, Lemmas 1-7),
+ * in busy-waiting or self-suspension mode, as the least fixed point of the
+ * respective recurrence, tasks taken in decreasing priority, and the verdict
+ * "every R_i <= D_i" (the response-time test of Sec. 4.3 / Sec. 6.1).
+ *
+ * Task model (Sec. 3): a taskset has n sporadic tasks with fixed priorities and
+ * constrained deadlines, each bound to one CPU core.  Task tau_i has C_i (sum of
+ * its CPU segments), period T_i, deadline D_i <= T_i, priority pi_i, eta^g_i GPU
+ * segments G_{i,j} = (G^m_{i,j}, G^e_{i,j}): CPU-side launch/driver work and pure
+ * GPU work (copies, kernels).  G_i is taken as sum_j (G^m_{i,j} + G^e_{i,j}).
+ * Per taskset: theta (GPU context-switch overhead, Def. 1), epsilon (runlist
+ * update delay, Def. 2) and the TSG time slice L (Eq. 3).
+ *
+ * All times are unsigned integer microseconds.  All arithmetic is exact
+ * integer arithmetic; results do not depend on launch shape or batch order.
+ *
+ * Plain C, no exceptions, no callbacks.  Every function returns GCAPS_OK (0) or
+ * a negative error code and never aborts.  A context is not thread-safe: use
+ * one context per host thread.
+ */
+#ifndef GCAPS_RTA_H
+#define GCAPS_RTA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gcaps_ctx gcaps_ctx; /* opaque: device id, stream, device scratch */
+
+/*
+ * One batch of tasksets of identical shape.  All pointers of one batch are
+ * either host pointers (gcaps_rta_batch) or device pointers on the context's
+ * device (gcaps_rta_batch_device).  The caller owns every buffer for the
+ * duration of the call (for the device entry point: until the work queued on
+ * the context's stream has completed); the library neither frees nor keeps them.
+ *
+ * Layout: per-taskset arrays have n_tasksets elements; per-task arrays are
+ * [n_tasksets][n_tasks] row-major, tasks in caller order (any priority order);
+ * per-segment arrays are [n_tasksets][n_tasks][max_gseg] row-major.
+ */
+typedef struct {
+  uint32_t n_tasksets; /* >= 1 */
+  uint32_t n_tasks;    /* n, 1..255, the same for every taskset of the batch */
+  uint32_t max_gseg;   /* S, 0..255: GPU-segment slots per task */
+  /* per taskset */
+  const uint32_t *theta_us; /* theta: context-switch overhead of round-robin TSG scheduling (Def. 1) */
+  const uint32_t *eps_us;   /* epsilon = alpha + theta: runlist update delay of GCAPS (Def. 2) */
+  const uint32_t *slice_us; /* L >= 1: TSG time slice (Eq. 3) */
+  /* per task */
+  const uint32_t *cpu_us;      /* C_i (Sec. 3) */
+  const uint8_t *n_cseg;       /* eta^c_i; part of the task tuple, used by no bound; may be NULL */
+  const uint32_t *period_us;   /* T_i >= 1 */
+  const uint32_t *deadline_us; /* 1 <= D_i <= T_i */
+  const int32_t *prio;         /* pi_i: larger = higher; equal values: lower caller index ranks higher */
+  const uint8_t *core;         /* CPU core of tau_i (partitioned scheduling) */
+  const uint8_t *n_gseg;       /* eta^g_i <= S; 0 = CPU-only task */
+  /* per segment; slots j >= eta^g_i are ignored; both may be NULL when S = 0 */
+  const uint32_t *gm_us; /* G^m_{i,j} */
+  const uint32_t *ge_us; /* G^e_{i,j} */
+} gcaps_batch;
+
+/* which analysis */
+enum { GCAPS_POLICY_GCAPS = 1, GCAPS_POLICY_RR = 2, GCAPS_POLICY_BOTH = 3 };
+enum { GCAPS_WAIT_BUSY = 0, GCAPS_WAIT_SUSPEND = 1 };
+
+/* error codes */
+enum {
+  GCAPS_OK = 0,
+  GCAPS_EINVAL = -1,  /* null pointer, zero or out-of-range size, unknown selector */
+  GCAPS_ETASK = -2,   /* a taskset violates the task model: T = 0, D = 0, D > T, L = 0, eta^g > S */
+  GCAPS_ENOMEM = -3,  /* host or device allocation failed */
+  GCAPS_EDEVICE = -4  /* a HIP call failed (no device, launch failure, ...) */
+};
+
+/* response-time sentinels in out_resp */
+#define GCAPS_RESP_MISS (-1)         /* first task in priority order whose bound exceeds D_i */
+#define GCAPS_RESP_NOT_ANALYSED (-2) /* every lower-priority task of that taskset */
+
+/*
+ * Creates a context on device `device_id`.  `hip_stream` is a hipStream_t on
+ * that device on which all work of the context is queued, or NULL for the
+ * device's default stream; the stream stays owned by the caller.
+ */
+int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream);
+
+/* Waits for the context's queued work, frees its device scratch.  NULL is allowed. */
+void gcaps_destroy(gcaps_ctx *ctx);
+
+/*
+ * Host-to-host entry point.  `batch` holds HOST pointers.  Copies the batch to
+ * the device, runs the analysis there, copies the results back, and returns
+ * when they are in place.
+ *   policy     GCAPS_POLICY_GCAPS, _RR or _BOTH;  npol = number of policies selected
+ *   wait_mode  GCAPS_WAIT_BUSY or GCAPS_WAIT_SUSPEND (applies to every selected policy)
+ *   out_resp   host int64 [npol][n_tasksets][n_tasks], tasks in caller order: R_i in
+ *              microseconds, or a sentinel.  Policies are stored in increasing
+ *              selector value (GCAPS before round-robin).
+ *   out_sched  host uint8 [npol][n_tasksets]: 1 iff every task met R_i <= D_i
+ *   first_bad_taskset  may be NULL; on GCAPS_ETASK receives the smallest index of
+ *              an invalid taskset
+ * On any error no output element is defined.
+ */
+int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                    int64_t *out_resp, uint8_t *out_sched, uint32_t *first_bad_taskset);
+
+/*
+ * Device-resident entry point: every pointer in `batch`, d_out_resp and
+ * d_out_sched is a DEVICE pointer on the context's device, with the layouts
+ * above.  The work is queued on the context's stream and the call returns
+ * without waiting for it.  Argument errors are reported at once; task-model
+ * violations are detected on the device and reported by gcaps_status().
+ * Outputs of an invalid taskset are undefined, all others are complete.
+ */
+int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                           int64_t *d_out_resp, uint8_t *d_out_sched);
+
+/*
+ * Waits for the context's stream and reports on the most recent
+ * gcaps_rta_batch_device call: GCAPS_OK, or GCAPS_ETASK with the smallest
+ * invalid taskset index in *first_bad_taskset (may be NULL), or GCAPS_EDEVICE.
+ */
+int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset);
+
+/*
+ * Optional pre-pass (off by default): group tasksets of similar total
+ * utilisation sum_i (C_i + G_i) / T_i into the same wavefronts before the
+ * analysis, so that lanes of a wavefront iterate and exit alike.  Results are
+ * identical either way; only the time differs.  enable: 0 or 1.
+ */
+int gcaps_set_binning(gcaps_ctx *ctx, int enable);
+
+/* Static description of an error code. */
+const char *gcaps_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,161 @@
+"""Thin ctypes binding of the C ABI in include/gcaps_rta.h.
+
+Argument marshalling only: every step of the analysis runs in the HIP kernels of
+``libgcaps_rta.so``.  There is no CPU fallback; if the library has not been built
+the import of this module fails.  Device memory and streams come from PyTorch.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgcaps_rta.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(hipcc --offload-arch=gfx950); there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+GCAPS_POLICY_GCAPS, GCAPS_POLICY_RR, GCAPS_POLICY_BOTH = 1, 2, 3
+GCAPS_WAIT_BUSY, GCAPS_WAIT_SUSPEND = 0, 1
+GCAPS_OK, GCAPS_EINVAL, GCAPS_ETASK, GCAPS_ENOMEM, GCAPS_EDEVICE = 0, -1, -2, -3, -4
+GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
+
+EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
+           "gcaps_set_binning", "gcaps_strerror"]
+
+_p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
+
+
+class gcaps_batch(ctypes.Structure):
+    _fields_ = [("n_tasksets", _u32), ("n_tasks", _u32), ("max_gseg", _u32),
+                ("theta_us", _p), ("eps_us", _p), ("slice_us", _p),
+                ("cpu_us", _p), ("n_cseg", _p), ("period_us", _p), ("deadline_us", _p), ("prio", _p),
+                ("core", _p), ("n_gseg", _p), ("gm_us", _p), ("ge_us", _p)]
+
+
+_lib.gcaps_create.restype = _int
+_lib.gcaps_create.argtypes = [ctypes.POINTER(_p), _int, _p]
+_lib.gcaps_destroy.restype = None
+_lib.gcaps_destroy.argtypes = [_p]
+_lib.gcaps_rta_batch.restype = _int
+_lib.gcaps_rta_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p, ctypes.POINTER(_u32)]
+_lib.gcaps_rta_batch_device.restype = _int
+_lib.gcaps_rta_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p]
+_lib.gcaps_status.restype = _int
+_lib.gcaps_status.argtypes = [_p, ctypes.POINTER(_u32)]
+_lib.gcaps_set_binning.restype = _int
+_lib.gcaps_set_binning.argtypes = [_p, _int]
+_lib.gcaps_strerror.restype = ctypes.c_char_p
+_lib.gcaps_strerror.argtypes = [_int]
+
+_FIELDS = [("theta_us", np.uint32, 1), ("eps_us", np.uint32, 1), ("slice_us", np.uint32, 1),
+           ("cpu_us", np.uint32, 2), ("period_us", np.uint32, 2), ("deadline_us", np.uint32, 2),
+           ("prio", np.int32, 2), ("core", np.uint8, 2), ("n_gseg", np.uint8, 2),
+           ("gm_us", np.uint32, 3), ("ge_us", np.uint32, 3)]
+
+
+class GcapsError(RuntimeError):
+    def __init__(self, code, first_bad=None):
+        msg = _lib.gcaps_strerror(code).decode()
+        if first_bad is not None:
+            msg += f" (first invalid taskset: {first_bad})"
+        super().__init__(msg)
+        self.code = code
+        self.first_bad = first_bad
+
+
+def gcaps_strerror(code):
+    return _lib.gcaps_strerror(code).decode()
+
+
+def npol(policy):
+    return bin(policy & 3).count("1")
+
+
+def gcaps_create(device_id=0, hip_stream=None):
+    """Returns an opaque context handle.  hip_stream: integer hipStream_t (e.g.
+    ``torch.cuda.Stream().cuda_stream``) or None for the default stream."""
+    h = _p()
+    rc = _lib.gcaps_create(ctypes.byref(h), device_id, _p(hip_stream) if hip_stream else None)
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    return h
+
+
+def gcaps_destroy(ctx):
+    _lib.gcaps_destroy(ctx)
+
+
+def gcaps_set_binning(ctx, enable):
+    rc = _lib.gcaps_set_binning(ctx, int(enable))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+
+
+def _shape(batch):
+    N, n = batch["cpu_us"].shape
+    S = batch["gm_us"].shape[2] if batch["gm_us"].ndim == 3 else 0
+    return int(N), int(n), int(S)
+
+
+def gcaps_rta_batch(ctx, batch, policy, wait_mode):
+    """Host entry point.  batch: dict of numpy arrays (see ``taskgen``).  Returns
+    (resp int64 [npol, N, n], sched uint8 [npol, N])."""
+    N, n, S = _shape(batch)
+    keep = {}
+    b = gcaps_batch(n_tasksets=N, n_tasks=n, max_gseg=S)
+    for name, dtype, ndim in _FIELDS:
+        a = np.ascontiguousarray(batch[name], dtype=dtype)
+        assert a.ndim == ndim and a.shape[0] == N, name
+        keep[name] = a
+        setattr(b, name, a.ctypes.data if a.size else None)
+    P = npol(policy)
+    resp = np.empty((P, N, n), np.int64)
+    sched = np.empty((P, N), np.uint8)
+    bad = _u32(0xFFFFFFFF)
+    rc = _lib.gcaps_rta_batch(ctx, ctypes.byref(b), policy, wait_mode, resp.ctypes.data, sched.ctypes.data,
+                              ctypes.byref(bad))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)
+    return resp, sched
+
+
+def to_device(batch, device="cuda:0"):
+    """Copies a numpy batch into torch device tensors (memory plumbing only)."""
+    import torch
+
+    out = {}
+    for name, dtype, _ in _FIELDS:
+        a = np.ascontiguousarray(batch[name], dtype=dtype)
+        t = torch.from_numpy(a.view(np.int32) if dtype == np.uint32 else a)
+        out[name] = t.to(device)
+    return out
+
+
+def gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched):
+    """Device entry point.  dbatch: dict of torch device tensors with the batch layout;
+    d_resp: int64 [npol, N, n], d_sched: uint8 [npol, N] device tensors.  Queues the work
+    on the context's stream and returns; call ``gcaps_status`` to wait and check."""
+    N, n = dbatch["cpu_us"].shape
+    S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
+    b = gcaps_batch(n_tasksets=int(N), n_tasks=int(n), max_gseg=int(S))
+    for name, _, _ in _FIELDS:
+        t = dbatch[name]
+        assert t.is_cuda and t.is_contiguous(), name
+        setattr(b, name, t.data_ptr() if t.numel() else None)
+    P = npol(policy)
+    assert d_resp.is_cuda and d_resp.is_contiguous() and d_resp.numel() == P * N * n and d_resp.element_size() == 8
+    assert d_sched.is_cuda and d_sched.is_contiguous() and d_sched.numel() == P * N and d_sched.element_size() == 1
+    rc = _lib.gcaps_rta_batch_device(ctx, ctypes.byref(b), policy, wait_mode, d_resp.data_ptr(), d_sched.data_ptr())
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+
+
+def gcaps_status(ctx):
+    bad = _u32(0xFFFFFFFF)
+    rc = _lib.gcaps_status(ctx, ctypes.byref(bad))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)

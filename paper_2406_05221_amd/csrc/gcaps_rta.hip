@@ -1,0 +1,280 @@
+/*
+ * gcaps_rta: C ABI and host logic of the batched response-time analysis for
+ * gfx950 (see include/gcaps_rta.h for the contract of every entry point).
+ *
+ * Host side: argument checks, a grow-only pool of device scratch per context,
+ * kernel launches on the context's stream.  Every step of the analysis runs in
+ * the kernels; there is no host fallback.
+ */
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "gcaps_rta.h"
+
+#include "rta_wide.hip.inc"
+
+namespace {
+
+typedef unsigned int u32;
+typedef unsigned long long u64;
+
+struct DeviceBuffer {
+  void *ptr = nullptr;
+  size_t bytes = 0;
+  /* grow-only: keeps the allocation when it is already large enough */
+  int reserve(size_t want) {
+    if (want <= bytes) return GCAPS_OK;
+    if (ptr) {
+      if (hipFree(ptr) != hipSuccess) return GCAPS_EDEVICE;
+      ptr = nullptr;
+      bytes = 0;
+    }
+    if (hipMalloc(&ptr, want) != hipSuccess) {
+      (void)hipGetLastError();
+      ptr = nullptr;
+      return GCAPS_ENOMEM;
+    }
+    bytes = want;
+    return GCAPS_OK;
+  }
+  void release() {
+    if (ptr) (void)hipFree(ptr);
+    ptr = nullptr;
+    bytes = 0;
+  }
+};
+
+int npol(int policy) { return ((policy & 1) ? 1 : 0) + ((policy & 2) ? 1 : 0); }
+
+}  // namespace
+
+struct gcaps_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  int n_cu = 0;
+  int binning = 0;
+  DeviceBuffer status;       /* u32 first_bad */
+  DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
+  DeviceBuffer staging_in, staging_out; /* device copies for the host entry point */
+  u32 *host_status = nullptr; /* pinned */
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+  }
+  ~DeviceGuard() {
+    if (ok && prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int check_batch(const gcaps_batch *b, int policy, int wait_mode, const void *out_resp, const void *out_sched) {
+  if (!b || !out_resp || !out_sched) return GCAPS_EINVAL;
+  if (b->n_tasksets == 0 || b->n_tasks == 0 || b->n_tasks > 255 || b->max_gseg > 255) return GCAPS_EINVAL;
+  if (!b->theta_us || !b->eps_us || !b->slice_us || !b->cpu_us || !b->period_us || !b->deadline_us ||
+      !b->prio || !b->core || !b->n_gseg)
+    return GCAPS_EINVAL;
+  if (b->max_gseg > 0 && (!b->gm_us || !b->ge_us)) return GCAPS_EINVAL;
+  if (policy < GCAPS_POLICY_GCAPS || policy > GCAPS_POLICY_BOTH) return GCAPS_EINVAL;
+  if (wait_mode != GCAPS_WAIT_BUSY && wait_mode != GCAPS_WAIT_SUSPEND) return GCAPS_EINVAL;
+  return GCAPS_OK;
+}
+
+/* lanes the wide kernel is launched with: enough to fill the chip, bounded so that
+ * its scratch columns stay modest */
+u32 wide_slots(const gcaps_ctx *ctx, u32 n_tasksets) {
+  u32 cap = (u32)ctx->n_cu * 8u * 256u;
+  u32 want = (n_tasksets + 255u) / 256u * 256u;
+  return want < cap ? want : cap;
+}
+
+int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                uint8_t *d_sched, const u32 *d_list, const u32 *d_list_count, u32 max_items) {
+  const u32 slots = wide_slots(ctx, max_items);
+  const size_t col = (size_t)slots * b->n_tasks;
+  const size_t bytes = col * (4 * sizeof(u32) + 3 * sizeof(u64));
+  int rc = ctx->wide_scratch.reserve(bytes);
+  if (rc != GCAPS_OK) return rc;
+  char *base = (char *)ctx->wide_scratch.ptr;
+  wide::Scratch ws;
+  ws.CGm = (u64 *)base;
+  ws.Ge = ws.CGm + col;
+  ws.K = ws.Ge + col;
+  ws.T = (u32 *)(ws.K + col);
+  ws.D = ws.T + col;
+  ws.meta = ws.D + col;
+  ws.R = ws.meta + col;
+  ws.n_slots = slots;
+  hipLaunchKernelGGL(wide::rta_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, policy,
+                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+/* Clears the per-call device words with a kernel (not a memset node) so that a caller
+ * may capture the launches of one call into a HIP graph. */
+__global__ void reset_status_kernel(u32 *status) {
+  if (threadIdx.x == 0) status[0] = 0xffffffffu;
+}
+
+int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+               uint8_t *d_sched) {
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr);
+  if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+  return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, b->n_tasksets);
+}
+
+}  // namespace
+
+extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
+  if (!out) return GCAPS_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  if (device_id < 0 || device_id >= count) return GCAPS_EINVAL;
+  gcaps_ctx *ctx = new (std::nothrow) gcaps_ctx;
+  if (!ctx) return GCAPS_ENOMEM;
+  ctx->device = device_id;
+  ctx->stream = (hipStream_t)hip_stream;
+  DeviceGuard guard(device_id);
+  int rc = guard.ok ? GCAPS_OK : GCAPS_EDEVICE;
+  hipDeviceProp_t prop;
+  if (rc == GCAPS_OK && hipGetDeviceProperties(&prop, device_id) != hipSuccess) rc = GCAPS_EDEVICE;
+  if (rc == GCAPS_OK) {
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    rc = ctx->status.reserve(256);
+  }
+  if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, sizeof(u32), hipHostMallocDefault) != hipSuccess)
+    rc = GCAPS_ENOMEM;
+  if (rc != GCAPS_OK) {
+    (void)hipGetLastError();
+    ctx->status.release();
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return GCAPS_OK;
+}
+
+extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
+  if (!ctx) return;
+  DeviceGuard guard(ctx->device);
+  (void)hipStreamSynchronize(ctx->stream);
+  ctx->status.release();
+  ctx->wide_scratch.release();
+  ctx->staging_in.release();
+  ctx->staging_out.release();
+  if (ctx->host_status) (void)hipHostFree(ctx->host_status);
+  delete ctx;
+}
+
+extern "C" int gcaps_set_binning(gcaps_ctx *ctx, int enable) {
+  if (!ctx || (enable != 0 && enable != 1)) return GCAPS_EINVAL;
+  ctx->binning = enable;
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                                      int64_t *d_out_resp, uint8_t *d_out_sched) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_batch(batch, policy, wait_mode, d_out_resp, d_out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  return run_device(ctx, batch, policy, wait_mode, d_out_resp, d_out_sched);
+}
+
+extern "C" int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset) {
+  if (!ctx) return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  if (hipMemcpyAsync(ctx->host_status, ctx->status.ptr, sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+          hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  if (*ctx->host_status != 0xffffffffu) {
+    if (first_bad_taskset) *first_bad_taskset = *ctx->host_status;
+    return GCAPS_ETASK;
+  }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                               int64_t *out_resp, uint8_t *out_sched, uint32_t *first_bad_taskset) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_batch(batch, policy, wait_mode, out_resp, out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+
+  const size_t N = batch->n_tasksets, n = batch->n_tasks, S = batch->max_gseg;
+  const size_t P = (size_t)npol(policy);
+  /* one staging allocation, every array aligned to 256 bytes */
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t sz_ts = up(N * 4), sz_task4 = up(N * n * 4), sz_task1 = up(N * n), sz_seg = up(N * n * S * 4);
+  const size_t in_bytes = 3 * sz_ts + 4 * sz_task4 + 2 * sz_task1 + 2 * sz_seg;
+  const size_t resp_bytes = up(P * N * n * 8), sched_bytes = up(P * N);
+  rc = ctx->staging_in.reserve(in_bytes);
+  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(resp_bytes + sched_bytes);
+  if (rc != GCAPS_OK) return rc;
+
+  char *cur = (char *)ctx->staging_in.ptr;
+  bool ok = true;
+  auto put = [&](const void *src, size_t bytes, size_t reserved) -> const void * {
+    void *dst = cur;
+    cur += reserved;
+    if (bytes && hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) ok = false;
+    return dst;
+  };
+  gcaps_batch d = *batch;
+  d.theta_us = (const u32 *)put(batch->theta_us, N * 4, sz_ts);
+  d.eps_us = (const u32 *)put(batch->eps_us, N * 4, sz_ts);
+  d.slice_us = (const u32 *)put(batch->slice_us, N * 4, sz_ts);
+  d.cpu_us = (const u32 *)put(batch->cpu_us, N * n * 4, sz_task4);
+  d.period_us = (const u32 *)put(batch->period_us, N * n * 4, sz_task4);
+  d.deadline_us = (const u32 *)put(batch->deadline_us, N * n * 4, sz_task4);
+  d.prio = (const int32_t *)put(batch->prio, N * n * 4, sz_task4);
+  d.core = (const uint8_t *)put(batch->core, N * n, sz_task1);
+  d.n_gseg = (const uint8_t *)put(batch->n_gseg, N * n, sz_task1);
+  d.n_cseg = nullptr;
+  d.gm_us = S ? (const u32 *)put(batch->gm_us, N * n * S * 4, sz_seg) : nullptr;
+  d.ge_us = S ? (const u32 *)put(batch->ge_us, N * n * S * 4, sz_seg) : nullptr;
+  if (!ok) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  int64_t *d_resp = (int64_t *)ctx->staging_out.ptr;
+  uint8_t *d_sched = (uint8_t *)ctx->staging_out.ptr + resp_bytes;
+  rc = run_device(ctx, &d, policy, wait_mode, d_resp, d_sched);
+  if (rc != GCAPS_OK) return rc;
+  rc = gcaps_status(ctx, first_bad_taskset);
+  if (rc != GCAPS_OK) return rc;
+  if (hipMemcpyAsync(out_resp, d_resp, P * N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_sched, d_sched, P * N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  return GCAPS_OK;
+}
+
+extern "C" const char *gcaps_strerror(int code) {
+  switch (code) {
+    case GCAPS_OK: return "success";
+    case GCAPS_EINVAL: return "invalid argument (null pointer, size out of range or unknown selector)";
+    case GCAPS_ETASK: return "a taskset violates the task model (T = 0, D = 0, D > T, L = 0 or eta^g > S)";
+    case GCAPS_ENOMEM: return "host or device allocation failed";
+    case GCAPS_EDEVICE: return "a HIP runtime call failed";
+    default: return "unknown gcaps error code";
+  }
+}

@@ -1,0 +1,160 @@
+/*
+ * Seeded synthetic taskset generator (host only).  It produces INPUTS in the
+ * task model of Sec. 3 following the generation recipe of Sec. 6.1 (number of
+ * tasks per CPU, UUniFast utilisation split per CPU, uniformly drawn period and
+ * number of GPU segments, rate-monotonic priorities); it contains none of the
+ * response-time analysis.  Both the CPU oracle's tests and the GPU library's
+ * tests and benchmark draw their inputs from here.
+ *
+ * Every taskset is generated from its own counter-based stream
+ * (seed, stream id, taskset index) -> splitmix64, so any taskset can be
+ * regenerated alone and the result does not depend on the thread count.
+ */
+#include <stdint.h>
+
+#include <algorithm>
+#include <cmath>
+#include <thread>
+#include <vector>
+
+namespace {
+
+struct Rng {
+  uint64_t s;
+  static uint64_t mix(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  }
+  Rng(uint64_t seed, uint64_t stream, uint64_t index) {
+    s = mix(seed + 0x9E3779B97F4A7C15ull);
+    s = mix(s ^ (stream + 0x632BE59BD9B4E019ull));
+    s = mix(s ^ (index * 0xD1342543DE82EF95ull + 1));
+  }
+  uint64_t next() { /* splitmix64 */
+    s += 0x9E3779B97F4A7C15ull;
+    return mix(s);
+  }
+  double uniform() { return (double)(next() >> 11) * (1.0 / 9007199254740992.0); } /* [0,1) */
+  double uniform(double lo, double hi) { return lo + (hi - lo) * uniform(); }
+  uint32_t integer(uint32_t lo, uint32_t hi) { /* inclusive */
+    return lo + (uint32_t)(uniform() * (double)(hi - lo + 1));
+  }
+};
+
+struct Spec {
+  uint64_t seed, stream, first_index;
+  uint32_t n_tasksets, n_cores, tasks_per_core, max_gseg;
+  double util_lo, util_hi;
+  const double *util_fixed; /* per taskset, or null */
+  uint32_t eta_lo, eta_hi;
+  double share_lo, share_hi;
+  const double *share_fixed;
+  uint32_t t_lo, t_hi;
+  uint32_t ovh_lo, ovh_hi;
+  const uint32_t *ovh_fixed;
+  uint32_t slice;
+  const uint32_t *slice_fixed;
+};
+
+struct Out {
+  uint32_t *theta, *eps, *slice, *cpu, *period, *deadline;
+  int32_t *prio;
+  uint8_t *core, *n_gseg;
+  uint32_t *gm, *ge;
+};
+
+void one_taskset(const Spec &sp, const Out &o, uint32_t k) {
+  Rng rng(sp.seed, sp.stream, sp.first_index + k);
+  const uint32_t n = sp.n_cores * sp.tasks_per_core;
+  const uint32_t S = sp.max_gseg;
+  const size_t to = (size_t)k * n;
+
+  uint32_t ovh = sp.ovh_fixed ? sp.ovh_fixed[k] : rng.integer(sp.ovh_lo, sp.ovh_hi);
+  o.theta[k] = ovh;
+  o.eps[k] = ovh;
+  o.slice[k] = sp.slice_fixed ? sp.slice_fixed[k] : sp.slice;
+
+  const double ln_lo = std::log((double)sp.t_lo), ln_hi = std::log((double)sp.t_hi);
+  for (uint32_t c = 0; c < sp.n_cores; ++c) {
+    double U = sp.util_fixed ? sp.util_fixed[k] : rng.uniform(sp.util_lo, sp.util_hi);
+    /* UUniFast: utilisations of the tasks of this core, summing to U */
+    double sum = U;
+    for (uint32_t j = 0; j < sp.tasks_per_core; ++j) {
+      const uint32_t i = c * sp.tasks_per_core + j;
+      double u;
+      if (j + 1 < sp.tasks_per_core) {
+        double next = sum * std::pow(rng.uniform(), 1.0 / (double)(sp.tasks_per_core - 1 - j));
+        u = sum - next;
+        sum = next;
+      } else {
+        u = sum;
+      }
+      double t = std::floor(std::exp(rng.uniform(ln_lo, ln_hi)));
+      uint32_t T = (uint32_t)std::min((double)sp.t_hi, std::max((double)sp.t_lo, t));
+      uint32_t eta = rng.integer(sp.eta_lo, sp.eta_hi);
+      uint32_t W = (uint32_t)std::floor(u * (double)T + 0.5); /* total WCET C + G */
+      W = std::max(W, 2 * eta + 1);
+      double share = sp.share_fixed ? sp.share_fixed[k] : rng.uniform(sp.share_lo, sp.share_hi);
+      uint32_t g = (uint32_t)std::floor(share * (double)W + 0.5);
+      g = std::min(std::max(g, 2 * eta), W - 1);
+      o.cpu[to + i] = W - g;
+      o.period[to + i] = T;
+      o.deadline[to + i] = T;
+      o.core[to + i] = (uint8_t)c;
+      o.n_gseg[to + i] = (uint8_t)eta;
+      for (uint32_t s = 0; s < S; ++s) {
+        uint32_t gj = 0;
+        if (s < eta) gj = g / eta + (s < g % eta ? 1 : 0);
+        o.gm[(to + i) * S + s] = gj / 2;      /* launch / copy half */
+        o.ge[(to + i) * S + s] = gj - gj / 2; /* kernel half */
+      }
+    }
+  }
+  /* rate-monotonic priorities over the whole taskset: shorter period = higher,
+   * equal periods: lower index higher.  Larger value = higher priority. */
+  for (uint32_t i = 0; i < n; ++i) {
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n; ++j)
+      if (o.period[to + j] < o.period[to + i] || (o.period[to + j] == o.period[to + i] && j < i)) ++rank;
+    o.prio[to + i] = (int32_t)(n - rank);
+  }
+}
+
+}  // namespace
+
+extern "C" int taskgen_generate(uint64_t seed, uint64_t stream, uint64_t first_index,
+                                uint32_t n_tasksets, uint32_t n_cores, uint32_t tasks_per_core,
+                                uint32_t max_gseg, double util_lo, double util_hi,
+                                const double *util_fixed, uint32_t eta_lo, uint32_t eta_hi,
+                                double share_lo, double share_hi, const double *share_fixed,
+                                uint32_t t_lo, uint32_t t_hi, uint32_t ovh_lo, uint32_t ovh_hi,
+                                const uint32_t *ovh_fixed, uint32_t slice, const uint32_t *slice_fixed,
+                                int threads, uint32_t *theta_us, uint32_t *eps_us, uint32_t *slice_us,
+                                uint32_t *cpu_us, uint32_t *period_us, uint32_t *deadline_us,
+                                int32_t *prio, uint8_t *core, uint8_t *n_gseg, uint32_t *gm_us,
+                                uint32_t *ge_us) {
+  if (n_tasksets == 0 || n_cores == 0 || n_cores > 255 || tasks_per_core == 0 ||
+      n_cores * tasks_per_core > 255 || eta_lo > eta_hi || eta_hi > max_gseg || t_lo == 0 ||
+      t_lo > t_hi || ovh_lo > ovh_hi || util_lo > util_hi || share_lo > share_hi)
+    return -1;
+  Spec sp{seed, stream, first_index, n_tasksets, n_cores, tasks_per_core, max_gseg, util_lo, util_hi,
+          util_fixed, eta_lo, eta_hi, share_lo, share_hi, share_fixed, t_lo, t_hi, ovh_lo, ovh_hi,
+          ovh_fixed, slice, slice_fixed};
+  Out o{theta_us, eps_us, slice_us, cpu_us, period_us, deadline_us, prio, core, n_gseg, gm_us, ge_us};
+  if (threads < 1) threads = 1;
+  if ((uint32_t)threads > n_tasksets) threads = (int)n_tasksets;
+  auto work = [&](int w) {
+    uint32_t lo = (uint32_t)((uint64_t)n_tasksets * w / threads);
+    uint32_t hi = (uint32_t)((uint64_t)n_tasksets * (w + 1) / threads);
+    for (uint32_t k = lo; k < hi; ++k) one_taskset(sp, o, k);
+  };
+  if (threads == 1) {
+    work(0);
+  } else {
+    std::vector<std::thread> pool;
+    for (int w = 0; w < threads; ++w) pool.emplace_back(work, w);
+    for (auto &t : pool) t.join();
+  }
+  return 0;
+}

@@ -1,0 +1,149 @@
+"""GPU library against the CPU oracle, bit for bit: every response time (int64 microseconds,
+sentinels included) and every schedulable flag, through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+GCAPS, RR, BOTH, BUSY, SUSPEND = 1, 2, 3, 0, 1
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2406_05221_amd import binding as B
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    yield B, ctx, stream
+    B.gcaps_destroy(ctx)
+
+
+def compare(oracle, B, ctx, batch, policy=BOTH, waits=(BUSY, SUSPEND)):
+    for wait in waits:
+        want_r, want_s, _ = oracle.rta_batch(batch, policy, wait, threads=16)
+        got_r, got_s = B.gcaps_rta_batch(ctx, batch, policy, wait)
+        bad = np.argwhere(got_r != want_r)
+        assert bad.size == 0, (wait, bad[:5], got_r[tuple(bad[0])], want_r[tuple(bad[0])])
+        assert (got_s == want_s).all()
+
+
+@pytest.mark.parametrize("k,N", [(1, None), (2, None), (3, 20_000), (4, 3_000), (5, 21_600)])
+def test_named_workloads(oracle, gpu, k, N):
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    print(f"workload {k} N={N}", flush=True)
+    compare(oracle, B, ctx, taskgen.config(k, N))
+
+
+def relaxed_workload(N, seed, n_cores=4, per_core=5, S=3):
+    """Like workload 3 but with long periods and small overheads, so that a good part of the
+    tasksets is schedulable under GCAPS and the fixed-point iterations run long."""
+    from paper_2406_05221_amd import taskgen
+    return taskgen.generate(N, n_cores=n_cores, tasks_per_core=per_core, max_gseg=S, util=(0.25, 0.85), eta=(0, S),
+                            share=(0.05, 0.5), period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024,
+                            seed=seed, stream=77)
+
+
+def few_gpu_tasks_workload(N, seed):
+    """Few GPU-using tasks and long periods: mostly schedulable under round-robin as well."""
+    from paper_2406_05221_amd import taskgen
+    return taskgen.generate(N, n_cores=4, tasks_per_core=4, max_gseg=2, util=(0.2, 0.7), eta=(0, 1),
+                            share=(0.05, 0.3), period=(50_000, 1_000_000), overhead=(0, 20), slice_us=256,
+                            seed=seed, stream=78)
+
+
+@pytest.mark.parametrize("policy", [GCAPS, RR, BOTH])
+def test_mostly_schedulable_tasksets(oracle, gpu, policy):
+    B, ctx, _ = gpu
+    batch = relaxed_workload(5_003, seed=policy)
+    want_s = oracle.rta_batch(batch, GCAPS, SUSPEND, threads=16)[1]
+    assert 0.2 < want_s.mean() < 0.98
+    compare(oracle, B, ctx, batch, policy)
+    batch = few_gpu_tasks_workload(5_003, seed=policy)
+    want_s = oracle.rta_batch(batch, RR, BUSY, threads=16)[1]
+    assert 0.2 < want_s.mean() < 0.98
+    compare(oracle, B, ctx, batch, policy)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 0), (1, 1, 1), (2, 1, 2), (3, 7, 1), (8, 10, 5), (5, 51, 2)])
+def test_shapes_and_ragged_batches(oracle, gpu, shape):
+    B, ctx, _ = gpu
+    cores, per_core, S = shape
+    for N in (1, 63, 64, 65, 257):
+        batch = relaxed_workload(N, seed=N, n_cores=cores, per_core=per_core, S=S)
+        compare(oracle, B, ctx, batch)
+
+
+def test_priority_ties_and_cpu_only_tasks(oracle, gpu):
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(5)
+    batch = relaxed_workload(2_000, seed=9)
+    batch["prio"] = rng.integers(-3, 4, batch["prio"].shape).astype(np.int32)
+    batch["n_gseg"] = np.where(rng.random(batch["n_gseg"].shape) < 0.4, 0, batch["n_gseg"]).astype(np.uint8)
+    batch["deadline_us"] = (batch["period_us"] * rng.uniform(0.5, 1.0, batch["period_us"].shape)).astype(np.uint32)
+    batch["core"] = rng.integers(0, 3, batch["core"].shape).astype(np.uint8)
+    compare(oracle, B, ctx, batch)
+
+
+def test_values_beyond_24_bits(oracle, gpu):
+    """Periods of hours, nanosecond-like slices, overheads near 2^32: exact all the same."""
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(6)
+    batch = relaxed_workload(1_500, seed=3, n_cores=2, per_core=4, S=2)
+    scale = rng.choice([1, 1, 300, 4000], size=(1500, 1)).astype(np.uint64)
+    for key in ("cpu_us", "period_us", "deadline_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale, 2**32 - 1).astype(np.uint32)
+    for key in ("gm_us", "ge_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale[:, :, None], 2**32 - 1).astype(np.uint32)
+    batch["slice_us"] = rng.choice([1, 7, 1024, 2**31], size=1500).astype(np.uint32)
+    batch["theta_us"] = rng.choice([0, 200, 2**32 - 1], size=1500).astype(np.uint32)
+    batch["eps_us"] = rng.choice([0, 200, 2**31], size=1500).astype(np.uint32)
+    compare(oracle, B, ctx, batch)
+    big = 2**32 - 1
+    one = dict(theta_us=[big], eps_us=[big], slice_us=[1], cpu_us=[[big, 5]], period_us=[[big, big]],
+               deadline_us=[[big, big]], prio=[[2, 1]], core=[[0, 0]], n_gseg=[[3, 3]],
+               gm_us=[[[big] * 3] * 2], ge_us=[[[big] * 3] * 2])
+    one = {k: np.array(v) for k, v in one.items()}
+    compare(oracle, B, ctx, one)
+
+
+def test_invalid_taskset_is_reported(gpu):
+    B, ctx, _ = gpu
+    batch = relaxed_workload(300, seed=1)
+    for key, value in (("period_us", 0), ("deadline_us", 0), ("slice_us", 0), ("n_gseg", 200)):
+        bad = {k: v.copy() for k, v in batch.items()}
+        if key == "slice_us":
+            bad[key][211] = value
+            bad[key][250] = value
+        else:
+            bad[key][211, 3] = value
+            bad[key][250, 0] = value
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_rta_batch(ctx, bad, BOTH, BUSY)
+        assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 211
+    bad = {k: v.copy() for k, v in batch.items()}
+    bad["deadline_us"][7, 2] = bad["period_us"][7, 2] + 1
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_rta_batch(ctx, bad, GCAPS, SUSPEND)
+    assert e.value.first_bad == 7
+    # the context stays usable
+    B.gcaps_rta_batch(ctx, batch, BOTH, BUSY)
+
+
+def test_device_entry_point_matches_host_entry_point(oracle, gpu):
+    import torch
+    from paper_2406_05221_amd import taskgen
+    B, ctx, stream = gpu
+    batch = taskgen.config(3, 10_000, first_index=500_000)
+    d = B.to_device(batch)
+    N, n = batch["cpu_us"].shape
+    for policy in (GCAPS, RR, BOTH):
+        P = B.npol(policy)
+        d_resp = torch.full((P, N, n), -7, dtype=torch.int64, device="cuda:0")
+        d_sched = torch.full((P, N), 9, dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        B.gcaps_rta_batch_device(ctx, d, policy, SUSPEND, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        want_r, want_s, _ = oracle.rta_batch(batch, policy, SUSPEND, threads=16)
+        assert (d_resp.cpu().numpy() == want_r).all() and (d_sched.cpu().numpy() == want_s).all()

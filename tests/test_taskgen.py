@@ -1,0 +1,56 @@
+"""The synthetic generator: determinism, shapes and the structure the workloads promise."""
+import numpy as np
+import pytest
+
+from paper_2406_05221_amd import taskgen
+
+
+@pytest.mark.parametrize("k,N", [(1, 1000), (2, 9000), (3, 5000), (4, 500), (5, 2160)])
+def test_workload_structure(k, N):
+    b = taskgen.config(k, N)
+    cores, per_core, S = taskgen.CONFIG_SHAPES[k]
+    n = cores * per_core
+    assert b["cpu_us"].shape == (N, n) and b["gm_us"].shape == (N, n, S)
+    assert (b["deadline_us"] == b["period_us"]).all()
+    assert (b["n_gseg"] >= 1).all() and (b["n_gseg"] <= S).all()
+    # unused slots are zero; used slots split a segment into launch/copy and kernel halves
+    used = np.arange(S)[None, None, :] < b["n_gseg"][:, :, None]
+    assert (b["gm_us"][~used] == 0).all() and (b["ge_us"][~used] == 0).all()
+    assert ((b["ge_us"] - b["gm_us"])[used] <= 1).all() and (b["ge_us"][used] >= 1).all()
+    # rate-monotonic, unique ranks 1..n
+    assert (np.sort(b["prio"], axis=1) == np.arange(1, n + 1)).all()
+    order = np.argsort(-b["prio"], axis=1)
+    assert (np.diff(np.take_along_axis(b["period_us"], order, 1).astype(np.int64), axis=1) >= 0).all()
+    # tasks_per_core tasks on each core
+    assert (b["core"] == np.repeat(np.arange(cores), per_core)[None, :]).all()
+    assert (b["theta_us"] == b["eps_us"]).all()
+
+
+def test_utilisation_per_core_matches_request():
+    b = taskgen.config(1)
+    w = b["cpu_us"].astype(np.float64) + b["gm_us"].sum(2) + b["ge_us"].sum(2)
+    u = (w / b["period_us"]).reshape(1000, 2, 3).sum(2)
+    assert abs(u.mean() - 0.4) < 0.005 and u.max() < 0.42
+    b = taskgen.config(2)
+    w = b["cpu_us"].astype(np.float64) + b["gm_us"].sum(2) + b["ge_us"].sum(2)
+    u = (w / b["period_us"]).reshape(9, 1000, 4, 4).sum(3).mean((1, 2))
+    assert np.allclose(u, 0.1 * np.arange(1, 10), atol=0.01)
+
+
+def test_any_taskset_can_be_regenerated_alone():
+    full = taskgen.config(3, 3000, threads=3)
+    part = taskgen.config(3, 100, first_index=1234, threads=1)
+    for key in full:
+        assert (full[key][1234:1334] == part[key]).all(), key
+    five = taskgen.config(5, 400)
+    tail = taskgen.config(5, 100, first_index=300)
+    for key in five:
+        assert (five[key][300:] == tail[key]).all(), key
+    # grid cell of workload 5 follows the taskset index
+    assert set(np.unique(five["slice_us"])) == {512, 1024, 2048}
+    assert set(np.unique(five["theta_us"])) == {50, 200, 500}
+
+
+def test_seed_changes_the_draw():
+    a, b = taskgen.config(1, 50, seed=0), taskgen.config(1, 50, seed=1)
+    assert (a["period_us"] != b["period_us"]).any()
