@@ -134,6 +134,14 @@ int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy,
 int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset);
 
 /*
+ * Diagnostics of the most recent gcaps_rta_batch_device / gcaps_rta_batch call
+ * (waits for the stream): how many of its tasksets had numbers outside the
+ * 24-bit fast kernel's range and were analysed by the general 64-bit kernel
+ * instead.  Results are exact on both routes; the count only explains speed.
+ */
+int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count);
+
+/*
  * Optional pre-pass (off by default): group tasksets of similar total
  * utilisation sum_i (C_i + G_i) / T_i into the same wavefronts before the
  * analysis, so that lanes of a wavefront iterate and exit alike.  Results are

@@ -24,7 +24,7 @@ GCAPS_OK, GCAPS_EINVAL, GCAPS_ETASK, GCAPS_ENOMEM, GCAPS_EDEVICE = 0, -1, -2, -3
 GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
-           "gcaps_set_binning", "gcaps_strerror"]
+           "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -46,6 +46,8 @@ _lib.gcaps_rta_batch_device.restype = _int
 _lib.gcaps_rta_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p]
 _lib.gcaps_status.restype = _int
 _lib.gcaps_status.argtypes = [_p, ctypes.POINTER(_u32)]
+_lib.gcaps_last_wide_count.restype = _int
+_lib.gcaps_last_wide_count.argtypes = [_p, ctypes.POINTER(_u32)]
 _lib.gcaps_set_binning.restype = _int
 _lib.gcaps_set_binning.argtypes = [_p, _int]
 _lib.gcaps_strerror.restype = ctypes.c_char_p
@@ -159,3 +161,11 @@ def gcaps_status(ctx):
     rc = _lib.gcaps_status(ctx, ctypes.byref(bad))
     if rc != GCAPS_OK:
         raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)
+
+
+def gcaps_last_wide_count(ctx):
+    c = _u32(0)
+    rc = _lib.gcaps_last_wide_count(ctx, ctypes.byref(c))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    return c.value

@@ -8,11 +8,13 @@
  */
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <new>
 
 #include "gcaps_rta.h"
 
 #include "rta_wide.hip.inc"
+#include "rta_fast.hip.inc"
 
 namespace {
 
@@ -54,7 +56,14 @@ struct gcaps_ctx {
   hipStream_t stream = nullptr;
   int n_cu = 0;
   int binning = 0;
-  DeviceBuffer status;       /* u32 first_bad */
+  u32 screen_tasks = 3;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
+  bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
+  u32 last_n_tasksets = 0;
+  int lds_limit = 65536;     /* dynamic LDS a workgroup may ask for */
+  DeviceBuffer status;       /* u32 first_bad, u32 wide_count */
+  DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
+  DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
+  size_t lds_total = 65536;  /* LDS of one CU */
   DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
   DeviceBuffer staging_in, staging_out; /* device copies for the host entry point */
   u32 *host_status = nullptr; /* pinned */
@@ -119,14 +128,71 @@ int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
 /* Clears the per-call device words with a kernel (not a memset node) so that a caller
  * may capture the launches of one call into a HIP graph. */
 __global__ void reset_status_kernel(u32 *status) {
-  if (threadIdx.x == 0) status[0] = 0xffffffffu;
+  if (threadIdx.x == 0) {
+    status[0] = 0xffffffffu; /* smallest invalid taskset index */
+    status[1] = 0;           /* length of the list for the 64-bit kernel */
+    status[2] = 0;           /* length of the list for the second fast launch */
+  }
 }
+
+template <int TS, bool LISTED>
+int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                uint8_t *d_sched, u32 kr, u32 blocks) {
+  const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
+  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                     (u32 *)ctx->deep_list.ptr, kr);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+/* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
+int tile_width(const gcaps_ctx *ctx, u32 n, u32 kr) {
+  for (int ts = 64; ts >= 16; ts /= 2)
+    if (fast::lds_bytes(n, kr, (u32)ts) <= (size_t)ctx->lds_limit) return ts;
+  return 0;
+}
+
 
 int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                uint8_t *d_sched) {
   hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr);
   if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
-  return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, b->n_tasksets);
+  const u32 n = b->n_tasks, N = b->n_tasksets;
+  const int ts_deep = n <= fast::kMaxTasks ? tile_width(ctx, n, n) : 0;
+  ctx->wide_only = ts_deep == 0;
+  ctx->last_n_tasksets = N;
+  if (ts_deep == 0) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
+  int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
+  if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)N * sizeof(u32));
+  if (rc != GCAPS_OK) return rc;
+
+  /* first launch: every taskset, the kr highest-priority tasks only */
+  const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
+  const int ts_screen = tile_width(ctx, n, kr);
+  const u32 tiles = (N + (u32)ts_screen - 1) / (u32)ts_screen;
+  rc = ts_screen == 64 ? launch_fast<64, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
+     : ts_screen == 32 ? launch_fast<32, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
+                       : launch_fast<16, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles);
+  if (rc != GCAPS_OK) return rc;
+
+  /* second launch: the tasksets still alive, in full; persistent workgroups walk the list */
+  if (kr < n) {
+    const size_t lds = fast::lds_bytes(n, n, (u32)ts_deep);
+    u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > 8) per_cu = 8;
+    u32 blocks = (u32)ctx->n_cu * per_cu;
+    const u32 max_tiles = (N + (u32)ts_deep - 1) / (u32)ts_deep;
+    if (blocks > max_tiles) blocks = max_tiles;
+    rc = ts_deep == 64 ? launch_fast<64, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks)
+       : ts_deep == 32 ? launch_fast<32, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks)
+                       : launch_fast<16, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks);
+    if (rc != GCAPS_OK) return rc;
+  }
+  /* whatever the fast launches handed over is redone in 64 bit; usually nothing */
+  const u32 *count = (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT;
+  const u32 items = N < 65536u ? N : 65536u;
+  return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count, items);
 }
 
 }  // namespace
@@ -144,6 +210,10 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (!ctx) return GCAPS_ENOMEM;
   ctx->device = device_id;
   ctx->stream = (hipStream_t)hip_stream;
+  if (const char *e = getenv("GCAPS_SCREEN_TASKS")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1 && v <= 255) ctx->screen_tasks = (u32)v;
+  }
   DeviceGuard guard(device_id);
   int rc = guard.ok ? GCAPS_OK : GCAPS_EDEVICE;
   hipDeviceProp_t prop;
@@ -151,6 +221,21 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (rc == GCAPS_OK) {
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     rc = ctx->status.reserve(256);
+  }
+  if (rc == GCAPS_OK) {
+    /* the fast kernel's tiles live in dynamic LDS: raise the per-workgroup limit to what the CU has */
+    size_t want = prop.sharedMemPerBlock;
+    if (prop.maxSharedMemoryPerMultiProcessor > want) want = prop.maxSharedMemoryPerMultiProcessor;
+    if (want > 160u * 1024u) want = 160u * 1024u;
+    const void *kernels[6] = {(const void *)fast::rta_fast_kernel<64, false>, (const void *)fast::rta_fast_kernel<32, false>,
+                              (const void *)fast::rta_fast_kernel<16, false>, (const void *)fast::rta_fast_kernel<64, true>,
+                              (const void *)fast::rta_fast_kernel<32, true>, (const void *)fast::rta_fast_kernel<16, true>};
+    bool raised = want > 65536;
+    for (int k = 0; k < 6 && raised; ++k)
+      raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
+    (void)hipGetLastError();
+    ctx->lds_limit = raised ? (int)want : 65536;
+    ctx->lds_total = want > 65536 ? want : 65536;
   }
   if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, sizeof(u32), hipHostMallocDefault) != hipSuccess)
     rc = GCAPS_ENOMEM;
@@ -170,6 +255,8 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
   (void)hipStreamSynchronize(ctx->stream);
   ctx->status.release();
   ctx->wide_scratch.release();
+  ctx->wide_list.release();
+  ctx->deep_list.release();
   ctx->staging_in.release();
   ctx->staging_out.release();
   if (ctx->host_status) (void)hipHostFree(ctx->host_status);
@@ -206,6 +293,20 @@ extern "C" int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset) {
     if (first_bad_taskset) *first_bad_taskset = *ctx->host_status;
     return GCAPS_ETASK;
   }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count) {
+  if (!ctx || !count) return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  if (hipMemcpyAsync(ctx->host_status, (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT, sizeof(u32), hipMemcpyDeviceToHost,
+                     ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  *count = ctx->wide_only ? ctx->last_n_tasksets : *ctx->host_status;
   return GCAPS_OK;
 }
 

@@ -34,6 +34,8 @@ def test_named_workloads(oracle, gpu, k, N):
     B, ctx, _ = gpu
     print(f"workload {k} N={N}", flush=True)
     compare(oracle, B, ctx, taskgen.config(k, N))
+    # the named workloads fit the 24-bit fast kernel entirely
+    assert B.gcaps_last_wide_count(ctx) == 0
 
 
 def relaxed_workload(N, seed, n_cores=4, per_core=5, S=3):
@@ -60,6 +62,7 @@ def test_mostly_schedulable_tasksets(oracle, gpu, policy):
     want_s = oracle.rta_batch(batch, GCAPS, SUSPEND, threads=16)[1]
     assert 0.2 < want_s.mean() < 0.98
     compare(oracle, B, ctx, batch, policy)
+    assert B.gcaps_last_wide_count(ctx) == 0
     batch = few_gpu_tasks_workload(5_003, seed=policy)
     want_s = oracle.rta_batch(batch, RR, BUSY, threads=16)[1]
     assert 0.2 < want_s.mean() < 0.98
@@ -100,6 +103,7 @@ def test_values_beyond_24_bits(oracle, gpu):
     batch["theta_us"] = rng.choice([0, 200, 2**32 - 1], size=1500).astype(np.uint32)
     batch["eps_us"] = rng.choice([0, 200, 2**31], size=1500).astype(np.uint32)
     compare(oracle, B, ctx, batch)
+    assert 100 < B.gcaps_last_wide_count(ctx) < 1500  # both kernels took part
     big = 2**32 - 1
     one = dict(theta_us=[big], eps_us=[big], slice_us=[1], cpu_us=[[big, 5]], period_us=[[big, big]],
                deadline_us=[[big, big]], prio=[[2, 1]], core=[[0, 0]], n_gseg=[[3, 3]],
