@@ -135,14 +135,29 @@ __global__ void reset_status_kernel(u32 *status) {
   }
 }
 
+template <int TS, bool LISTED, int NP>
+int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                   uint8_t *d_sched, u32 kr, u32 blocks) {
+  const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
+  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
+                     policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
+                     (u32 *)ctx->wide_list.ptr, (u32 *)ctx->deep_list.ptr, kr);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+/* NP: register slots for the terms of one task (ranks analysed in this launch, rounded up);
+ * only the 64-wide tile has register variants, everything else loops over LDS */
 template <int TS, bool LISTED>
 int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr, u32 blocks) {
-  const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
-  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
-                     (u32 *)ctx->deep_list.ptr, kr);
-  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+  if constexpr (TS == 64) {
+    if (kr <= 4) return launch_fast_np<TS, LISTED, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 8) return launch_fast_np<TS, LISTED, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 16) return launch_fast_np<TS, LISTED, 16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 24) return launch_fast_np<TS, LISTED, 24>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 32) return launch_fast_np<TS, LISTED, 32>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+  }
+  return launch_fast_np<TS, LISTED, 0>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
 }
 
 /* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
@@ -227,11 +242,17 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     size_t want = prop.sharedMemPerBlock;
     if (prop.maxSharedMemoryPerMultiProcessor > want) want = prop.maxSharedMemoryPerMultiProcessor;
     if (want > 160u * 1024u) want = 160u * 1024u;
-    const void *kernels[6] = {(const void *)fast::rta_fast_kernel<64, false>, (const void *)fast::rta_fast_kernel<32, false>,
-                              (const void *)fast::rta_fast_kernel<16, false>, (const void *)fast::rta_fast_kernel<64, true>,
-                              (const void *)fast::rta_fast_kernel<32, true>, (const void *)fast::rta_fast_kernel<16, true>};
+    const void *kernels[] = {
+        (const void *)fast::rta_fast_kernel<64, false, 0>,  (const void *)fast::rta_fast_kernel<64, true, 0>,
+        (const void *)fast::rta_fast_kernel<64, false, 4>,  (const void *)fast::rta_fast_kernel<64, true, 4>,
+        (const void *)fast::rta_fast_kernel<64, false, 8>,  (const void *)fast::rta_fast_kernel<64, true, 8>,
+        (const void *)fast::rta_fast_kernel<64, false, 16>, (const void *)fast::rta_fast_kernel<64, true, 16>,
+        (const void *)fast::rta_fast_kernel<64, false, 24>, (const void *)fast::rta_fast_kernel<64, true, 24>,
+        (const void *)fast::rta_fast_kernel<64, false, 32>, (const void *)fast::rta_fast_kernel<64, true, 32>,
+        (const void *)fast::rta_fast_kernel<32, false, 0>,  (const void *)fast::rta_fast_kernel<32, true, 0>,
+        (const void *)fast::rta_fast_kernel<16, false, 0>,  (const void *)fast::rta_fast_kernel<16, true, 0>};
     bool raised = want > 65536;
-    for (int k = 0; k < 6 && raised; ++k)
+    for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
     (void)hipGetLastError();
     ctx->lds_limit = raised ? (int)want : 65536;
