@@ -10,6 +10,7 @@
 
 #include <cstdlib>
 #include <new>
+#include <type_traits>
 
 #include "gcaps_rta.h"
 
