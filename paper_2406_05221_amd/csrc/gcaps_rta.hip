@@ -136,11 +136,11 @@ __global__ void reset_status_kernel(u32 *status) {
   }
 }
 
-template <int TS, bool LISTED, int NP>
+template <int TS, bool LISTED, int NP, bool CACHE = false>
 int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                    uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
-  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
+  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP, CACHE>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
                      (u32 *)ctx->wide_list.ptr, (u32 *)ctx->deep_list.ptr, kr);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
@@ -152,6 +152,9 @@ template <int TS, bool LISTED>
 int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr, u32 blocks) {
   if constexpr (TS == 64) {
+    if constexpr (!LISTED)
+      if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs)
+        return launch_fast_np<TS, LISTED, 4, true>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 4) return launch_fast_np<TS, LISTED, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 8) return launch_fast_np<TS, LISTED, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 16) return launch_fast_np<TS, LISTED, 16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
@@ -244,14 +247,15 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     if (prop.maxSharedMemoryPerMultiProcessor > want) want = prop.maxSharedMemoryPerMultiProcessor;
     if (want > 160u * 1024u) want = 160u * 1024u;
     const void *kernels[] = {
-        (const void *)fast::rta_fast_kernel<64, false, 0>,  (const void *)fast::rta_fast_kernel<64, true, 0>,
-        (const void *)fast::rta_fast_kernel<64, false, 4>,  (const void *)fast::rta_fast_kernel<64, true, 4>,
-        (const void *)fast::rta_fast_kernel<64, false, 8>,  (const void *)fast::rta_fast_kernel<64, true, 8>,
-        (const void *)fast::rta_fast_kernel<64, false, 16>, (const void *)fast::rta_fast_kernel<64, true, 16>,
-        (const void *)fast::rta_fast_kernel<64, false, 24>, (const void *)fast::rta_fast_kernel<64, true, 24>,
-        (const void *)fast::rta_fast_kernel<64, false, 32>, (const void *)fast::rta_fast_kernel<64, true, 32>,
-        (const void *)fast::rta_fast_kernel<32, false, 0>,  (const void *)fast::rta_fast_kernel<32, true, 0>,
-        (const void *)fast::rta_fast_kernel<16, false, 0>,  (const void *)fast::rta_fast_kernel<16, true, 0>};
+        (const void *)fast::rta_fast_kernel<64, false, 0, false>,  (const void *)fast::rta_fast_kernel<64, true, 0, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 4, false>,  (const void *)fast::rta_fast_kernel<64, true, 4, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 8, false>,  (const void *)fast::rta_fast_kernel<64, true, 8, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 16, false>, (const void *)fast::rta_fast_kernel<64, true, 16, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 24, false>, (const void *)fast::rta_fast_kernel<64, true, 24, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 32, false>, (const void *)fast::rta_fast_kernel<64, true, 32, false>,
+        (const void *)fast::rta_fast_kernel<32, false, 0, false>,  (const void *)fast::rta_fast_kernel<32, true, 0, false>,
+        (const void *)fast::rta_fast_kernel<16, false, 0, false>,  (const void *)fast::rta_fast_kernel<16, true, 0, false>,
+        (const void *)fast::rta_fast_kernel<64, false, 4, true>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
