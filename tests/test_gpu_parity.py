@@ -151,3 +151,55 @@ def test_device_entry_point_matches_host_entry_point(oracle, gpu):
         B.gcaps_status(ctx)
         want_r, want_s, _ = oracle.rta_batch(batch, policy, SUSPEND, threads=16)
         assert (d_resp.cpu().numpy() == want_r).all() and (d_sched.cpu().numpy() == want_s).all()
+
+
+# ---- full sizes, in the launch configuration the benchmark times (device entry point, both policies) ----
+def full_size_cases():
+    from paper_2406_05221_amd import taskgen
+    cases = [(1, 0, 1000), (2, 0, 9000), (3, 0, 1_000_000), (4, 0, 100_000)]
+    cases += [(5, k * 1_000_000, 1_000_000) for k in range(10)]  # workload 5 streamed in 1M batches
+    return cases
+
+
+@pytest.mark.parametrize("k,first,N", full_size_cases())
+def test_full_size_workloads_device_entry(oracle, gpu, k, first, N):
+    """Every response time and flag of every taskset of the five workloads, both waiting modes."""
+    import torch
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    print(f"workload {k} tasksets [{first}, {first + N})", flush=True)
+    batch = taskgen.config(k, N, first_index=first)
+    d = B.to_device(batch)
+    n = batch["cpu_us"].shape[1]
+    d_resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+    d_sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+    for wait in (BUSY, SUSPEND):
+        d_resp.fill_(-7)
+        d_sched.fill_(9)
+        torch.cuda.synchronize()
+        B.gcaps_rta_batch_device(ctx, d, BOTH, wait, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        assert B.gcaps_last_wide_count(ctx) == 0
+        want_r, want_s, _ = oracle.rta_batch(batch, BOTH, wait, threads=16)
+        got_r = d_resp.cpu().numpy()
+        assert np.array_equal(got_r, want_r), np.argwhere(got_r != want_r)[:5]
+        assert np.array_equal(d_sched.cpu().numpy(), want_s)
+        # properties that hold at any size: sentinels are consistent with the flags
+        miss = (got_r == -1).sum(axis=2)
+        assert ((miss == 0) == (d_sched.cpu().numpy() == 1)).all() and miss.max() <= 1
+
+
+def test_binning_does_not_change_results(oracle, gpu):
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    batch = taskgen.config(5, 50_000, first_index=123_456)
+    want = oracle.rta_batch(batch, BOTH, SUSPEND, threads=16)
+    try:
+        B.gcaps_set_binning(ctx, 1)
+        got_r, got_s = B.gcaps_rta_batch(ctx, batch, BOTH, SUSPEND)
+        assert np.array_equal(got_r, want[0]) and np.array_equal(got_s, want[1])
+        compare(oracle, B, ctx, relaxed_workload(7_001, seed=11))
+    finally:
+        B.gcaps_set_binning(ctx, 0)
+    got_r, got_s = B.gcaps_rta_batch(ctx, batch, BOTH, SUSPEND)
+    assert np.array_equal(got_r, want[0]) and np.array_equal(got_s, want[1])
