@@ -16,6 +16,7 @@
 
 #include "rta_wide.hip.inc"
 #include "rta_fast.hip.inc"
+#include "rta_bin.hip.inc"
 
 namespace {
 
@@ -64,6 +65,9 @@ struct gcaps_ctx {
   DeviceBuffer status;       /* u32 first_bad, u32 wide_count */
   DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
   DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
+  DeviceBuffer deep_sorted;  /* the same list ordered by utilisation bucket (binning) */
+  DeviceBuffer bin_keys;     /* bucket of every list entry */
+  DeviceBuffer bin_hist;     /* 256 bucket offsets + 256 scatter cursors */
   size_t lds_total = 65536;  /* LDS of one CU */
   DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
   DeviceBuffer staging_in, staging_out; /* device copies for the host entry point */
@@ -140,9 +144,10 @@ template <int TS, bool LISTED, int NP, bool CACHE = false>
 int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                    uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
+  u32 *list = (u32 *)((LISTED && ctx->binning) ? ctx->deep_sorted.ptr : ctx->deep_list.ptr);
   hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP, CACHE>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
-                     (u32 *)ctx->wide_list.ptr, (u32 *)ctx->deep_list.ptr, kr);
+                     (u32 *)ctx->wide_list.ptr, list, kr);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -195,6 +200,25 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
   if (rc != GCAPS_OK) return rc;
 
   /* second launch: the tasksets still alive, in full; persistent workgroups walk the list */
+  if (kr < n && ctx->binning) {
+    /* counting sort of the list by utilisation bucket */
+    rc = ctx->deep_sorted.reserve((size_t)N * sizeof(u32));
+    if (rc == GCAPS_OK) rc = ctx->bin_keys.reserve((size_t)N * sizeof(u32));
+    if (rc == GCAPS_OK) rc = ctx->bin_hist.reserve(2 * bin::kBuckets * sizeof(u32));
+    if (rc != GCAPS_OK) return rc;
+    u32 *hist = (u32 *)ctx->bin_hist.ptr, *cursor = hist + bin::kBuckets;
+    const u32 *cnt = (const u32 *)ctx->status.ptr + fast::ST_DEEP_COUNT;
+    u32 kb = (N + 63u) / 64u;
+    if (kb > (u32)ctx->n_cu * 16u) kb = (u32)ctx->n_cu * 16u;
+    hipLaunchKernelGGL(bin::bin_clear_kernel, dim3(1), dim3(256), 0, ctx->stream, hist);
+    hipLaunchKernelGGL(bin::bin_key_kernel, dim3(kb), dim3(64), 0, ctx->stream, *b,
+                       (const u32 *)ctx->deep_list.ptr, cnt, (u32 *)ctx->bin_keys.ptr, hist);
+    hipLaunchKernelGGL(bin::bin_scan_kernel, dim3(1), dim3(64), 0, ctx->stream, hist, cursor);
+    hipLaunchKernelGGL(bin::bin_scatter_kernel, dim3(kb), dim3(64), 0, ctx->stream,
+                       (const u32 *)ctx->deep_list.ptr, cnt, (const u32 *)ctx->bin_keys.ptr, cursor,
+                       (u32 *)ctx->deep_sorted.ptr);
+    if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+  }
   if (kr < n) {
     const size_t lds = fast::lds_bytes(n, n, (u32)ts_deep);
     u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
@@ -283,6 +307,9 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
   ctx->wide_scratch.release();
   ctx->wide_list.release();
   ctx->deep_list.release();
+  ctx->deep_sorted.release();
+  ctx->bin_keys.release();
+  ctx->bin_hist.release();
   ctx->staging_in.release();
   ctx->staging_out.release();
   if (ctx->host_status) (void)hipHostFree(ctx->host_status);
