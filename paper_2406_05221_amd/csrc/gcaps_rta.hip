@@ -58,7 +58,10 @@ struct gcaps_ctx {
   hipStream_t stream = nullptr;
   int n_cu = 0;
   int binning = 0;
-  u32 screen_tasks = 3;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
+  u64 chunk_cap = 0;        /* GCAPS_CHUNK_TASKSETS: smaller chunks than the 32-bit limit needs (testing) */
+  u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
+  size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
+  u32 ts_offset = 0;                        /* first taskset of the current chunk */
   bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
   u32 last_n_tasksets = 0;
   int lds_limit = 65536;     /* dynamic LDS a workgroup may ask for */
@@ -126,28 +129,43 @@ int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   ws.R = ws.meta + col;
   ws.n_slots = slots;
   hipLaunchKernelGGL(wide::rta_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, policy,
-                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count);
+                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count,
+                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
 /* Clears the per-call device words with a kernel (not a memset node) so that a caller
  * may capture the launches of one call into a HIP graph. */
-__global__ void reset_status_kernel(u32 *status) {
+__global__ void reset_status_kernel(u32 *status, int first_chunk) {
   if (threadIdx.x == 0) {
-    status[0] = 0xffffffffu; /* smallest invalid taskset index */
-    status[1] = 0;           /* length of the list for the 64-bit kernel */
-    status[2] = 0;           /* length of the list for the second fast launch */
+    if (first_chunk) {
+      status[0] = 0xffffffffu; /* smallest invalid taskset index of the call */
+      status[3] = 0;           /* tasksets sent to the 64-bit kernel by earlier chunks */
+    } else {
+      status[3] += status[1];
+    }
+    status[1] = 0; /* length of the list for the 64-bit kernel */
+    status[2] = 0; /* length of the list for the second fast launch */
   }
 }
 
-template <int TS, bool LISTED, int NP, bool CACHE = false>
+template <int TS, bool LISTED, int NP>
 int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                    uint8_t *d_sched, u32 kr, u32 blocks) {
-  const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS);
+  const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS, false);
   u32 *list = (u32 *)((LISTED && ctx->binning) ? ctx->deep_sorted.ptr : ctx->deep_list.ptr);
-  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP, CACHE>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
+  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
-                     (u32 *)ctx->wide_list.ptr, list, kr);
+                     (u32 *)ctx->wide_list.ptr, list, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                  uint8_t *d_sched, u32 kr, u32 blocks) {
+  const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
+  hipLaunchKernelGGL(fast::rta_screen_kernel, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
+                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                     (u32 *)ctx->deep_list.ptr, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -159,7 +177,7 @@ int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   if constexpr (TS == 64) {
     if constexpr (!LISTED)
       if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs)
-        return launch_fast_np<TS, LISTED, 4, true>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+        return launch_screen(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 4) return launch_fast_np<TS, LISTED, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 8) return launch_fast_np<TS, LISTED, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 16) return launch_fast_np<TS, LISTED, 16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
@@ -172,19 +190,20 @@ int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
 /* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
 int tile_width(const gcaps_ctx *ctx, u32 n, u32 kr) {
   for (int ts = 64; ts >= 16; ts /= 2)
-    if (fast::lds_bytes(n, kr, (u32)ts) <= (size_t)ctx->lds_limit) return ts;
+    if (fast::lds_bytes(n, kr, (u32)ts, false) <= (size_t)ctx->lds_limit) return ts;
   return 0;
 }
 
 
-int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
-               uint8_t *d_sched) {
-  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr);
+/* one chunk: every array of it stays below 4 GiB, so the kernels index with 32 bits */
+int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+              uint8_t *d_sched, bool first_chunk) {
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr,
+                     first_chunk ? 1 : 0);
   if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   const u32 n = b->n_tasks, N = b->n_tasksets;
   const int ts_deep = n <= fast::kMaxTasks ? tile_width(ctx, n, n) : 0;
   ctx->wide_only = ts_deep == 0;
-  ctx->last_n_tasksets = N;
   if (ts_deep == 0) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
   int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
   if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)N * sizeof(u32));
@@ -220,7 +239,7 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
   if (kr < n) {
-    const size_t lds = fast::lds_bytes(n, n, (u32)ts_deep);
+    const size_t lds = fast::lds_bytes(n, n, (u32)ts_deep, false);
     u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 8) per_cu = 8;
@@ -238,6 +257,43 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
   return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count, items);
 }
 
+/* Splits a call into chunks of tasksets small enough for the kernels' 32-bit byte offsets:
+ * within a chunk every input array and each policy's block of responses stays below 4 GiB. */
+int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+               uint8_t *d_sched) {
+  const u64 n = b->n_tasks, S = b->max_gseg ? b->max_gseg : 1, N = b->n_tasksets;
+  u64 chunk = (1ull << 28) / n;                 /* 8-byte responses: N*n*8 < 2^31 */
+  const u64 by_seg = (1ull << 30) / (n * S);    /* 4-byte segments:  N*n*S*4 < 2^32 */
+  if (by_seg < chunk) chunk = by_seg;
+  if (ctx->chunk_cap && ctx->chunk_cap < chunk) chunk = ctx->chunk_cap;
+  if (chunk > 64) chunk &= ~63ull;
+  if (chunk < 1) chunk = 1;
+  ctx->resp_stride = (size_t)(N * n);
+  ctx->sched_stride = (size_t)N;
+  ctx->last_n_tasksets = b->n_tasksets;
+  for (u64 c0 = 0; c0 < N; c0 += chunk) {
+    gcaps_batch sub = *b;
+    const u64 cn = N - c0 < chunk ? N - c0 : chunk;
+    sub.n_tasksets = (u32)cn;
+    sub.theta_us += c0;
+    sub.eps_us += c0;
+    sub.slice_us += c0;
+    sub.cpu_us += c0 * n;
+    sub.period_us += c0 * n;
+    sub.deadline_us += c0 * n;
+    sub.prio += c0 * n;
+    sub.core += c0 * n;
+    sub.n_gseg += c0 * n;
+    if (sub.n_cseg) sub.n_cseg += c0 * n;
+    if (sub.gm_us) sub.gm_us += c0 * n * b->max_gseg;
+    if (sub.ge_us) sub.ge_us += c0 * n * b->max_gseg;
+    ctx->ts_offset = (u32)c0;
+    const int rc = run_chunk(ctx, &sub, policy, wait_mode, d_resp + c0 * n, d_sched + c0, c0 == 0);
+    if (rc != GCAPS_OK) return rc;
+  }
+  return GCAPS_OK;
+}
+
 }  // namespace
 
 extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
@@ -253,6 +309,10 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (!ctx) return GCAPS_ENOMEM;
   ctx->device = device_id;
   ctx->stream = (hipStream_t)hip_stream;
+  if (const char *e = getenv("GCAPS_CHUNK_TASKSETS")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1) ctx->chunk_cap = (u64)v;
+  }
   if (const char *e = getenv("GCAPS_SCREEN_TASKS")) {
     const long v = strtol(e, nullptr, 10);
     if (v >= 1 && v <= 255) ctx->screen_tasks = (u32)v;
@@ -271,15 +331,14 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     if (prop.maxSharedMemoryPerMultiProcessor > want) want = prop.maxSharedMemoryPerMultiProcessor;
     if (want > 160u * 1024u) want = 160u * 1024u;
     const void *kernels[] = {
-        (const void *)fast::rta_fast_kernel<64, false, 0, false>,  (const void *)fast::rta_fast_kernel<64, true, 0, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 4, false>,  (const void *)fast::rta_fast_kernel<64, true, 4, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 8, false>,  (const void *)fast::rta_fast_kernel<64, true, 8, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 16, false>, (const void *)fast::rta_fast_kernel<64, true, 16, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 24, false>, (const void *)fast::rta_fast_kernel<64, true, 24, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 32, false>, (const void *)fast::rta_fast_kernel<64, true, 32, false>,
-        (const void *)fast::rta_fast_kernel<32, false, 0, false>,  (const void *)fast::rta_fast_kernel<32, true, 0, false>,
-        (const void *)fast::rta_fast_kernel<16, false, 0, false>,  (const void *)fast::rta_fast_kernel<16, true, 0, false>,
-        (const void *)fast::rta_fast_kernel<64, false, 4, true>};
+        (const void *)fast::rta_fast_kernel<64, false, 0>,  (const void *)fast::rta_fast_kernel<64, true, 0>,
+        (const void *)fast::rta_fast_kernel<64, false, 4>,  (const void *)fast::rta_fast_kernel<64, true, 4>,
+        (const void *)fast::rta_fast_kernel<64, false, 8>,  (const void *)fast::rta_fast_kernel<64, true, 8>,
+        (const void *)fast::rta_fast_kernel<64, false, 16>, (const void *)fast::rta_fast_kernel<64, true, 16>,
+        (const void *)fast::rta_fast_kernel<64, false, 24>, (const void *)fast::rta_fast_kernel<64, true, 24>,
+        (const void *)fast::rta_fast_kernel<64, false, 32>, (const void *)fast::rta_fast_kernel<64, true, 32>,
+        (const void *)fast::rta_fast_kernel<32, false, 0>,  (const void *)fast::rta_fast_kernel<32, true, 0>,
+        (const void *)fast::rta_fast_kernel<16, false, 0>,  (const void *)fast::rta_fast_kernel<16, true, 0>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
@@ -287,7 +346,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     ctx->lds_limit = raised ? (int)want : 65536;
     ctx->lds_total = want > 65536 ? want : 65536;
   }
-  if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, sizeof(u32), hipHostMallocDefault) != hipSuccess)
+  if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, 4 * sizeof(u32), hipHostMallocDefault) != hipSuccess)
     rc = GCAPS_ENOMEM;
   if (rc != GCAPS_OK) {
     (void)hipGetLastError();
@@ -353,13 +412,13 @@ extern "C" int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count) {
   if (!ctx || !count) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT, sizeof(u32), hipMemcpyDeviceToHost,
-                     ctx->stream) != hipSuccess ||
+  if (hipMemcpyAsync(ctx->host_status, ctx->status.ptr, 4 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+          hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
     return GCAPS_EDEVICE;
   }
-  *count = ctx->wide_only ? ctx->last_n_tasksets : *ctx->host_status;
+  *count = ctx->wide_only ? ctx->last_n_tasksets : ctx->host_status[1] + ctx->host_status[3];
   return GCAPS_OK;
 }
 

@@ -203,3 +203,28 @@ def test_binning_does_not_change_results(oracle, gpu):
         B.gcaps_set_binning(ctx, 0)
     got_r, got_s = B.gcaps_rta_batch(ctx, batch, BOTH, SUSPEND)
     assert np.array_equal(got_r, want[0]) and np.array_equal(got_s, want[1])
+
+
+def test_chunked_calls(oracle, monkeypatch):
+    """Calls too large for 32-bit byte offsets are split into chunks of tasksets; forced here with
+    a small chunk size.  Policy strides, the invalid-taskset index and the 64-bit hand-over count
+    must all refer to the whole call."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "1000")
+    monkeypatch.setenv("GCAPS_SCREEN_TASKS", "2")
+    ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
+    try:
+        batch = relaxed_workload(4_321, seed=21)
+        batch["period_us"][[5, 1500, 4000], 0] = 2**23  # beyond the fast kernel's range: three chunks hand over
+        batch["deadline_us"][[5, 1500, 4000], 0] = 2**23
+        compare(oracle, B, ctx, batch)
+        assert B.gcaps_last_wide_count(ctx) == 3
+        compare(oracle, B, ctx, batch, policy=RR, waits=(BUSY,))
+        bad = {k: v.copy() for k, v in batch.items()}
+        bad["period_us"][3456, 7] = 0
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_rta_batch(ctx, bad, BOTH, BUSY)
+        assert e.value.first_bad == 3456
+    finally:
+        B.gcaps_destroy(ctx)
