@@ -69,6 +69,8 @@ struct gcaps_ctx {
   DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
   DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
   DeviceBuffer deep_sorted;  /* the same list ordered by utilisation bucket (binning) */
+  DeviceBuffer deep_compact; /* the same list made contiguous (binning) */
+  u32 region_cap = 0;        /* slots per region of deep_list in the current chunk */
   DeviceBuffer bin_keys;     /* bucket of every list entry */
   DeviceBuffer bin_hist;     /* 256 bucket offsets + 256 scatter cursors */
   size_t lds_total = 65536;  /* LDS of one CU */
@@ -145,18 +147,27 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
       status[3] += status[1];
     }
     status[1] = 0; /* length of the list for the 64-bit kernel */
-    status[2] = 0; /* length of the list for the second fast launch */
+    status[2] = 0; /* length of the compacted list for the second fast launch (binning only) */
   }
+  status[fast::ST_DEEP_COUNTS + threadIdx.x] = 0; /* per-region lengths of the list for the second fast launch */
+}
+
+/* the list between the two fast launches: regions filled by the first launch, or (binning) the
+ * contiguous list ordered by bucket */
+fast::ListSpec deep_list_spec(const gcaps_ctx *ctx, bool sorted) {
+  u32 *status = (u32 *)ctx->status.ptr;
+  if (sorted) return fast::ListSpec{(u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u};
+  return fast::ListSpec{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap};
 }
 
 template <int TS, bool LISTED, int NP>
 int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                    uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS, false);
-  u32 *list = (u32 *)((LISTED && ctx->binning) ? ctx->deep_sorted.ptr : ctx->deep_list.ptr);
+  fast::ListSpec dl = deep_list_spec(ctx, LISTED && ctx->binning);
   hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
-                     (u32 *)ctx->wide_list.ptr, list, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                     (u32 *)ctx->wide_list.ptr, dl, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -165,7 +176,7 @@ int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
   hipLaunchKernelGGL(fast::rta_screen_kernel, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
                      (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
-                     (u32 *)ctx->deep_list.ptr, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                     deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -206,7 +217,10 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   ctx->wide_only = ts_deep == 0;
   if (ts_deep == 0) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
   int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
-  if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)N * sizeof(u32));
+  /* tiles of the first launch go to the list regions round-robin: a region never overflows */
+  const u32 producer_tiles = (N + 15u) / 16u; /* the narrowest tile width */
+  ctx->region_cap = ((producer_tiles + fast::kListRegions - 1) / fast::kListRegions) * 64u;
+  if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32));
   if (rc != GCAPS_OK) return rc;
 
   /* first launch: every taskset, the kr highest-priority tasks only */
@@ -226,15 +240,21 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     if (rc == GCAPS_OK) rc = ctx->bin_hist.reserve(2 * bin::kBuckets * sizeof(u32));
     if (rc != GCAPS_OK) return rc;
     u32 *hist = (u32 *)ctx->bin_hist.ptr, *cursor = hist + bin::kBuckets;
-    const u32 *cnt = (const u32 *)ctx->status.ptr + fast::ST_DEEP_COUNT;
+    u32 *status = (u32 *)ctx->status.ptr;
+    const u32 *cnt = status + fast::ST_DEEP_TOTAL;
+    rc = ctx->deep_compact.reserve((size_t)N * sizeof(u32));
+    if (rc != GCAPS_OK) return rc;
     u32 kb = (N + 63u) / 64u;
     if (kb > (u32)ctx->n_cu * 16u) kb = (u32)ctx->n_cu * 16u;
+    hipLaunchKernelGGL(bin::compact_kernel, dim3(fast::kListRegions), dim3(256), 0, ctx->stream,
+                       (const u32 *)ctx->deep_list.ptr, (const u32 *)(status + fast::ST_DEEP_COUNTS),
+                       fast::kListRegions, ctx->region_cap, (u32 *)ctx->deep_compact.ptr, status + fast::ST_DEEP_TOTAL);
     hipLaunchKernelGGL(bin::bin_clear_kernel, dim3(1), dim3(256), 0, ctx->stream, hist);
     hipLaunchKernelGGL(bin::bin_key_kernel, dim3(kb), dim3(64), 0, ctx->stream, *b,
-                       (const u32 *)ctx->deep_list.ptr, cnt, (u32 *)ctx->bin_keys.ptr, hist);
+                       (const u32 *)ctx->deep_compact.ptr, cnt, (u32 *)ctx->bin_keys.ptr, hist);
     hipLaunchKernelGGL(bin::bin_scan_kernel, dim3(1), dim3(64), 0, ctx->stream, hist, cursor);
     hipLaunchKernelGGL(bin::bin_scatter_kernel, dim3(kb), dim3(64), 0, ctx->stream,
-                       (const u32 *)ctx->deep_list.ptr, cnt, (const u32 *)ctx->bin_keys.ptr, cursor,
+                       (const u32 *)ctx->deep_compact.ptr, cnt, (const u32 *)ctx->bin_keys.ptr, cursor,
                        (u32 *)ctx->deep_sorted.ptr);
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
@@ -323,7 +343,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (rc == GCAPS_OK && hipGetDeviceProperties(&prop, device_id) != hipSuccess) rc = GCAPS_EDEVICE;
   if (rc == GCAPS_OK) {
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    rc = ctx->status.reserve(256);
+    rc = ctx->status.reserve(1024);
   }
   if (rc == GCAPS_OK) {
     /* the fast kernel's tiles live in dynamic LDS: raise the per-workgroup limit to what the CU has */
@@ -367,6 +387,7 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
   ctx->wide_list.release();
   ctx->deep_list.release();
   ctx->deep_sorted.release();
+  ctx->deep_compact.release();
   ctx->bin_keys.release();
   ctx->bin_hist.release();
   ctx->staging_in.release();
