@@ -16,6 +16,7 @@
 
 #include "rta_wide.hip.inc"
 #include "rta_fast.hip.inc"
+#include "rta_deep.hip.inc"
 #include "rta_bin.hip.inc"
 
 namespace {
@@ -160,12 +161,12 @@ fast::ListSpec deep_list_spec(const gcaps_ctx *ctx, bool sorted) {
   return fast::ListSpec{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap};
 }
 
-template <int TS, bool LISTED, int NP>
+template <int TS, int NP>
 int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                    uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS, false);
-  fast::ListSpec dl = deep_list_spec(ctx, LISTED && ctx->binning);
-  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, LISTED, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
+  fast::ListSpec dl = deep_list_spec(ctx, false);
+  hipLaunchKernelGGL((fast::rta_fast_kernel<TS, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
                      (u32 *)ctx->wide_list.ptr, dl, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
@@ -182,20 +183,42 @@ int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
 
 /* NP: register slots for the terms of one task (ranks analysed in this launch, rounded up);
  * only the 64-wide tile has register variants, everything else loops over LDS */
-template <int TS, bool LISTED>
+template <int TS>
 int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr, u32 blocks) {
   if constexpr (TS == 64) {
-    if constexpr (!LISTED)
-      if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs)
+    if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs)
         return launch_screen(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
-    if (kr <= 4) return launch_fast_np<TS, LISTED, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
-    if (kr <= 8) return launch_fast_np<TS, LISTED, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
-    if (kr <= 16) return launch_fast_np<TS, LISTED, 16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
-    if (kr <= 24) return launch_fast_np<TS, LISTED, 24>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
-    if (kr <= 32) return launch_fast_np<TS, LISTED, 32>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 4) return launch_fast_np<TS, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 8) return launch_fast_np<TS, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 16) return launch_fast_np<TS, 16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 24) return launch_fast_np<TS, 24>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+    if (kr <= 32) return launch_fast_np<TS, 32>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
   }
-  return launch_fast_np<TS, LISTED, 0>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+  return launch_fast_np<TS, 0>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
+}
+
+/* second launch: the listed tasksets in full, 16 per wavefront; persistent workgroups */
+int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                uint8_t *d_sched) {
+  const u32 n = b->n_tasks, N = b->n_tasksets;
+  const size_t lds = fast::deep_lds_bytes(n);
+  u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
+  if (per_cu < 1) per_cu = 1;
+  if (per_cu > 16) per_cu = 16;
+  u32 blocks = (u32)ctx->n_cu * per_cu;
+  const u32 max_tiles = (N + fast::kDeepTS - 1) / fast::kDeepTS + fast::kListRegions;
+  if (blocks > max_tiles) blocks = max_tiles;
+  const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
+  if (n <= 4 * fast::kDeepSlots)
+    hipLaunchKernelGGL((fast::rta_deep_kernel<(int)fast::kDeepSlots>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
+                       policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
+                       (u32 *)ctx->wide_list.ptr, dl, ctx->resp_stride, ctx->sched_stride);
+  else
+    hipLaunchKernelGGL((fast::rta_deep_kernel<0>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
+                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
+                       ctx->resp_stride, ctx->sched_stride);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
 /* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
@@ -213,9 +236,10 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
                      first_chunk ? 1 : 0);
   if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   const u32 n = b->n_tasks, N = b->n_tasksets;
-  const int ts_deep = n <= fast::kMaxTasks ? tile_width(ctx, n, n) : 0;
-  ctx->wide_only = ts_deep == 0;
-  if (ts_deep == 0) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
+  const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
+  const int ts_screen = n <= fast::kMaxTasks ? tile_width(ctx, n, kr) : 0;
+  ctx->wide_only = ts_screen == 0 || (kr < n && fast::deep_lds_bytes(n) > (size_t)ctx->lds_limit);
+  if (ctx->wide_only) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
   int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
   /* tiles of the first launch go to the list regions round-robin: a region never overflows */
   const u32 producer_tiles = (N + 15u) / 16u; /* the narrowest tile width */
@@ -224,12 +248,10 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   if (rc != GCAPS_OK) return rc;
 
   /* first launch: every taskset, the kr highest-priority tasks only */
-  const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
-  const int ts_screen = tile_width(ctx, n, kr);
   const u32 tiles = (N + (u32)ts_screen - 1) / (u32)ts_screen;
-  rc = ts_screen == 64 ? launch_fast<64, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
-     : ts_screen == 32 ? launch_fast<32, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
-                       : launch_fast<16, false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles);
+  rc = ts_screen == 64 ? launch_fast<64>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
+     : ts_screen == 32 ? launch_fast<32>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles)
+                       : launch_fast<16>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, tiles);
   if (rc != GCAPS_OK) return rc;
 
   /* second launch: the tasksets still alive, in full; persistent workgroups walk the list */
@@ -259,16 +281,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
   if (kr < n) {
-    const size_t lds = fast::lds_bytes(n, n, (u32)ts_deep, false);
-    u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
-    if (per_cu < 1) per_cu = 1;
-    if (per_cu > 8) per_cu = 8;
-    u32 blocks = (u32)ctx->n_cu * per_cu;
-    const u32 max_tiles = (N + (u32)ts_deep - 1) / (u32)ts_deep;
-    if (blocks > max_tiles) blocks = max_tiles;
-    rc = ts_deep == 64 ? launch_fast<64, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks)
-       : ts_deep == 32 ? launch_fast<32, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks)
-                       : launch_fast<16, true>(ctx, b, policy, wait_mode, d_resp, d_sched, n, blocks);
+    rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched);
     if (rc != GCAPS_OK) return rc;
   }
   /* whatever the fast launches handed over is redone in 64 bit; usually nothing */
@@ -351,14 +364,12 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     if (prop.maxSharedMemoryPerMultiProcessor > want) want = prop.maxSharedMemoryPerMultiProcessor;
     if (want > 160u * 1024u) want = 160u * 1024u;
     const void *kernels[] = {
-        (const void *)fast::rta_fast_kernel<64, false, 0>,  (const void *)fast::rta_fast_kernel<64, true, 0>,
-        (const void *)fast::rta_fast_kernel<64, false, 4>,  (const void *)fast::rta_fast_kernel<64, true, 4>,
-        (const void *)fast::rta_fast_kernel<64, false, 8>,  (const void *)fast::rta_fast_kernel<64, true, 8>,
-        (const void *)fast::rta_fast_kernel<64, false, 16>, (const void *)fast::rta_fast_kernel<64, true, 16>,
-        (const void *)fast::rta_fast_kernel<64, false, 24>, (const void *)fast::rta_fast_kernel<64, true, 24>,
-        (const void *)fast::rta_fast_kernel<64, false, 32>, (const void *)fast::rta_fast_kernel<64, true, 32>,
-        (const void *)fast::rta_fast_kernel<32, false, 0>,  (const void *)fast::rta_fast_kernel<32, true, 0>,
-        (const void *)fast::rta_fast_kernel<16, false, 0>,  (const void *)fast::rta_fast_kernel<16, true, 0>};
+        (const void *)fast::rta_fast_kernel<64, 0>,  (const void *)fast::rta_fast_kernel<64, 4>,
+        (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
+        (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
+        (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
+        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<(int)fast::kDeepSlots>,
+        (const void *)fast::rta_deep_kernel<0>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
