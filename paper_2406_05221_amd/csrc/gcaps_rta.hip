@@ -149,6 +149,7 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
     }
     status[1] = 0; /* length of the list for the 64-bit kernel */
     status[2] = 0; /* length of the compacted list for the second fast launch (binning only) */
+    status[4] = 0; /* next tile of the second fast launch */
   }
   status[fast::ST_DEEP_COUNTS + threadIdx.x] = 0; /* per-region lengths of the list for the second fast launch */
 }
@@ -210,14 +211,9 @@ int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   const u32 max_tiles = (N + fast::kDeepTS - 1) / fast::kDeepTS + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
   const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
-  if (n <= 4 * fast::kDeepSlots)
-    hipLaunchKernelGGL((fast::rta_deep_kernel<(int)fast::kDeepSlots>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
-                       policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
-                       (u32 *)ctx->wide_list.ptr, dl, ctx->resp_stride, ctx->sched_stride);
-  else
-    hipLaunchKernelGGL((fast::rta_deep_kernel<0>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
-                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                       ctx->resp_stride, ctx->sched_stride);
+  hipLaunchKernelGGL(fast::rta_deep_kernel, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
+                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
+                     ctx->resp_stride, ctx->sched_stride);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -368,8 +364,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
         (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
         (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
-        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<(int)fast::kDeepSlots>,
-        (const void *)fast::rta_deep_kernel<0>};
+        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
