@@ -211,9 +211,14 @@ int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   const u32 max_tiles = (N + fast::kDeepTS - 1) / fast::kDeepTS + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
   const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
-  hipLaunchKernelGGL(fast::rta_deep_kernel, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
-                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                     ctx->resp_stride, ctx->sched_stride);
+  if (wait_mode == GCAPS_WAIT_BUSY)
+    hipLaunchKernelGGL(fast::rta_deep_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
+                       ctx->resp_stride, ctx->sched_stride);
+  else
+    hipLaunchKernelGGL(fast::rta_deep_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
+                       ctx->resp_stride, ctx->sched_stride);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -364,7 +369,8 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
         (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
         (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
-        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel};
+        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<true>,
+        (const void *)fast::rta_deep_kernel<false>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
