@@ -201,7 +201,7 @@ int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
 
 /* second launch: the listed tasksets in full, 16 per wavefront; persistent workgroups */
 int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
-                uint8_t *d_sched) {
+                uint8_t *d_sched, u32 kr) {
   const u32 n = b->n_tasks, N = b->n_tasksets;
   const size_t lds = fast::deep_lds_bytes(n);
   u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
@@ -214,11 +214,11 @@ int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   if (wait_mode == GCAPS_WAIT_BUSY)
     hipLaunchKernelGGL(fast::rta_deep_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
                        (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                       ctx->resp_stride, ctx->sched_stride);
+                       kr, ctx->resp_stride, ctx->sched_stride);
   else
     hipLaunchKernelGGL(fast::rta_deep_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
                        (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                       ctx->resp_stride, ctx->sched_stride);
+                       kr, ctx->resp_stride, ctx->sched_stride);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -282,7 +282,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
   if (kr < n) {
-    rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched);
+    rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched, kr);
     if (rc != GCAPS_OK) return rc;
   }
   /* whatever the fast launches handed over is redone in 64 bit; usually nothing */
