@@ -61,6 +61,7 @@ struct gcaps_ctx {
   int binning = 0;
   u64 chunk_cap = 0;        /* GCAPS_CHUNK_TASKSETS: smaller chunks than the 32-bit limit needs (testing) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
+  u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
   size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
   u32 ts_offset = 0;                        /* first taskset of the current chunk */
   bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
@@ -199,27 +200,32 @@ int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   return launch_fast_np<TS, 0>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
 }
 
-/* second launch: the listed tasksets in full, 16 per wavefront; persistent workgroups */
-int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
-                uint8_t *d_sched, u32 kr) {
-  const u32 n = b->n_tasks, N = b->n_tasksets;
-  const size_t lds = fast::deep_lds_bytes(n);
+/* second launch: the listed tasksets in full, 64 / Q per wavefront; persistent workgroups */
+template <bool BUSY, int Q>
+int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_resp, uint8_t *d_sched, u32 kr) {
+  const u32 n = b->n_tasks, N = b->n_tasksets, ts = 64u / (u32)Q;
+  const size_t lds = fast::deep_lds_bytes(n, Q);
   u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
   if (per_cu < 1) per_cu = 1;
   if (per_cu > 16) per_cu = 16;
   u32 blocks = (u32)ctx->n_cu * per_cu;
-  const u32 max_tiles = (N + fast::kDeepTS - 1) / fast::kDeepTS + fast::kListRegions;
+  const u32 max_tiles = (N + ts - 1) / ts + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
   const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
-  if (wait_mode == GCAPS_WAIT_BUSY)
-    hipLaunchKernelGGL(fast::rta_deep_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                       kr, ctx->resp_stride, ctx->sched_stride);
-  else
-    hipLaunchKernelGGL(fast::rta_deep_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl,
-                       kr, ctx->resp_stride, ctx->sched_stride);
+  hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl, kr,
+                     ctx->resp_stride, ctx->sched_stride);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                uint8_t *d_sched, u32 kr) {
+  const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+  if (ctx->deep_lanes == 8)
+    return busy ? launch_deep_q<true, 8>(ctx, b, policy, d_resp, d_sched, kr)
+                : launch_deep_q<false, 8>(ctx, b, policy, d_resp, d_sched, kr);
+  return busy ? launch_deep_q<true, 4>(ctx, b, policy, d_resp, d_sched, kr)
+              : launch_deep_q<false, 4>(ctx, b, policy, d_resp, d_sched, kr);
 }
 
 /* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
@@ -239,7 +245,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   const u32 n = b->n_tasks, N = b->n_tasksets;
   const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
   const int ts_screen = n <= fast::kMaxTasks ? tile_width(ctx, n, kr) : 0;
-  ctx->wide_only = ts_screen == 0 || (kr < n && fast::deep_lds_bytes(n) > (size_t)ctx->lds_limit);
+  ctx->wide_only = ts_screen == 0 || (kr < n && fast::deep_lds_bytes(n, ctx->deep_lanes) > (size_t)ctx->lds_limit);
   if (ctx->wide_only) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
   int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
   /* tiles of the first launch go to the list regions round-robin: a region never overflows */
@@ -351,6 +357,10 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     const long v = strtol(e, nullptr, 10);
     if (v >= 1 && v <= 255) ctx->screen_tasks = (u32)v;
   }
+  if (const char *e = getenv("GCAPS_DEEP_LANES")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v == 4 || v == 8) ctx->deep_lanes = (u32)v;
+  }
   DeviceGuard guard(device_id);
   int rc = guard.ok ? GCAPS_OK : GCAPS_EDEVICE;
   hipDeviceProp_t prop;
@@ -369,8 +379,9 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
         (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
         (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
-        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<true>,
-        (const void *)fast::rta_deep_kernel<false>};
+        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<true, 4>,
+        (const void *)fast::rta_deep_kernel<false, 4>,        (const void *)fast::rta_deep_kernel<true, 8>,
+        (const void *)fast::rta_deep_kernel<false, 8>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
