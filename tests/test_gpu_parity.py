@@ -69,7 +69,8 @@ def test_mostly_schedulable_tasksets(oracle, gpu, policy):
     compare(oracle, B, ctx, batch, policy)
 
 
-@pytest.mark.parametrize("shape", [(1, 1, 0), (1, 1, 1), (2, 1, 2), (3, 7, 1), (8, 10, 5), (5, 51, 2)])
+@pytest.mark.parametrize("shape", [(1, 1, 0), (1, 1, 1), (2, 1, 2), (3, 7, 1), (8, 10, 5), (5, 51, 2), (2, 3, 11),
+                                   (3, 11, 7), (2, 17, 4), (4, 16, 3)])
 def test_shapes_and_ragged_batches(oracle, gpu, shape):
     B, ctx, _ = gpu
     cores, per_core, S = shape
@@ -228,3 +229,41 @@ def test_chunked_calls(oracle, monkeypatch):
         assert e.value.first_bad == 3456
     finally:
         B.gcaps_destroy(ctx)
+
+
+@pytest.mark.parametrize("screen_tasks,deep_lanes", [(1, 4), (3, 8), (4, 8), (6, 4), (6, 8), (9, 4), (64, 4)])
+def test_launch_split_knobs(oracle, monkeypatch, screen_tasks, deep_lanes):
+    """How many ranks the first launch analyses and how many lanes share a taskset in the second
+    are tuning knobs: results are the same for every setting, also where the second launch resumes
+    from more ranks than it has lanes per taskset, and where the first launch settles everything."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    monkeypatch.setenv("GCAPS_SCREEN_TASKS", str(screen_tasks))
+    monkeypatch.setenv("GCAPS_DEEP_LANES", str(deep_lanes))
+    ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
+    try:
+        compare(oracle, B, ctx, relaxed_workload(3_001, seed=31))
+        compare(oracle, B, ctx, relaxed_workload(517, seed=32, n_cores=3, per_core=11, S=5))
+        compare(oracle, B, ctx, few_gpu_tasks_workload(1_003, seed=33), policy=RR)
+        from paper_2406_05221_amd import taskgen
+        compare(oracle, B, ctx, taskgen.config(3, 10_000, first_index=500_000))
+    finally:
+        B.gcaps_destroy(ctx)
+
+
+def test_out_of_range_values_below_the_screened_ranks(oracle, gpu):
+    """Values outside the fast kernels' range in LOW-priority tasks only: the first launch does not
+    look at them, the second hands the taskset over to the 64-bit kernel when it gets there."""
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(8)
+    batch = relaxed_workload(2_000, seed=41, n_cores=4, per_core=10, S=2)
+    order = np.argsort(-batch["prio"], axis=1, kind="stable")
+    rows = np.arange(2_000)
+    low = order[rows, rng.integers(8, 40, 2_000)]
+    pick = rng.random(2_000) < 0.3
+    batch["prio"][rows[pick], low[pick]] = -(2**30)           # far below the 24-bit key range
+    pick2 = rng.random(2_000) < 0.2
+    batch["period_us"][rows[pick2], low[pick2]] = 2**24       # beyond the reciprocal's range
+    batch["deadline_us"][rows[pick2], low[pick2]] = 2**24
+    compare(oracle, B, ctx, batch)
+    assert B.gcaps_last_wide_count(ctx) > 0
