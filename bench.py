@@ -23,6 +23,23 @@ HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # CUs x SIMDs x lanes x clock: 32-bit integer lane-ops/s
 OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3), multiply-add, compare
 
+# HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
+# rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
+# counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
+# Valid only for the kernel sources the counters were taken with.
+MEASURED_TRAFFIC = dict(csrc_sha256=None, workload=3, tasksets=1_000_000, fetch_bytes=None, write_bytes=None)
+
+
+def csrc_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2406_05221_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".inc", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
 
 def algorithmic_bytes_per_taskset(n, S, npol):
     """Bytes the path must move per taskset: every input once, every output once."""
@@ -43,7 +60,14 @@ def main():
     ap.add_argument("--tasksets", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--binning", type=int, default=0, choices=[0, 1])
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
+                         "HBM byte counters collected over this command)")
+    ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
     args = ap.parse_args()
+    if args.print_csrc_hash:
+        print(csrc_sha256())
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is built and measured on ONE GPU; run it with --gpus 1 "
               "(tasksets are independent, more GPUs would each take a contiguous share)", file=sys.stderr)
@@ -100,6 +124,13 @@ def main():
                            sched_ratio_gcaps=float(d_sched[0].float().mean().item()),
                            sched_ratio_rr=float(d_sched[1].float().mean().item()),
                            tasksets_via_64bit_kernel=B.gcaps_last_wide_count(ctx))
+    if args.copy_calibration:
+        src = torch.zeros(2**28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     head = min(modes, key=lambda m: modes[m]["tasksets_per_s"])
     head_wait = B.GCAPS_WAIT_BUSY if head == "busy" else B.GCAPS_WAIT_SUSPEND
 
@@ -134,8 +165,13 @@ def main():
     m = modes[head]
     bytes_per_launch = algorithmic_bytes_per_taskset(n, S, P) * N
     achieved = bytes_per_launch / (m["device_ms_per_step"] * 1e-3) / 1e9
+    traffic = None
+    mt = MEASURED_TRAFFIC
+    if (mt["csrc_sha256"] and args.workload == mt["workload"] and N == mt["tasksets"] and not args.binning
+            and mt["csrc_sha256"] == csrc_sha256()):
+        traffic = mt["fetch_bytes"] + mt["write_bytes"]
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="gcaps_rta_batch_device (all launches of one step)",
+                    traffic=traffic, kernel="gcaps_rta_batch_device (all launches of one step)",
                     algorithmic_bytes_per_taskset=algorithmic_bytes_per_taskset(n, S, P))
     alu = None
     if terms_per_taskset is not None:
@@ -146,7 +182,7 @@ def main():
 
     out = dict(metric="tasksets analysed/sec (both RTAs), 1 MI355X", value=m["tasksets_per_s"], unit="tasksets/s",
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=m["wall_ms_per_step"],
-               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="u32/u64", data="synthetic",
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="u32", data="synthetic",
                config=dict(workload=f"workload {args.workload}: {N} tasksets, {cores} cores x {per_core} tasks/core, "
                                     f"up to {S} GPU segments/task, GCAPS + round-robin analyses, headline = slower "
                                     f"waiting mode ({head})",

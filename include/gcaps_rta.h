@@ -142,10 +142,11 @@ int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset);
 int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count);
 
 /*
- * Optional pre-pass (off by default): group tasksets of similar total
- * utilisation sum_i (C_i + G_i) / T_i into the same wavefronts before the
- * analysis, so that lanes of a wavefront iterate and exit alike.  Results are
- * identical either way; only the time differs.  enable: 0 or 1.
+ * Optional pre-pass (off by default): order the tasksets that need the second,
+ * full-depth launch by total utilisation sum_i (C_i + G_i) / T_i, so that the
+ * tasksets sharing a wavefront there iterate and exit alike.  Results are
+ * identical either way; only the time differs (on the measured workloads the
+ * pre-pass costs more than it saves).  enable: 0 or 1.
  */
 int gcaps_set_binning(gcaps_ctx *ctx, int enable);
 
