@@ -205,10 +205,16 @@ template <bool BUSY, int Q>
 int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_resp, uint8_t *d_sched, u32 kr) {
   const u32 n = b->n_tasks, N = b->n_tasksets, ts = 64u / (u32)Q;
   const size_t lds = fast::deep_lds_bytes(n, Q);
-  u32 per_cu = (u32)((size_t)ctx->lds_total / lds);
-  if (per_cu < 1) per_cu = 1;
-  if (per_cu > 16) per_cu = 16;
-  u32 blocks = (u32)ctx->n_cu * per_cu;
+  /* Exactly as many workgroups as are resident at once (LDS and registers both limit it): a
+   * workgroup's first tile is its own index, so one that had to wait for a free slot would start
+   * that tile only after the others have drained the queue. */
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fast::rta_deep_kernel<BUSY, Q>, 64, lds) != hipSuccess ||
+      per_cu < 1) {
+    (void)hipGetLastError();
+    per_cu = 1;
+  }
+  u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
   const u32 max_tiles = (N + ts - 1) / ts + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
   const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
