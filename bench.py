@@ -27,8 +27,8 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="ed248f9093008f809cfeb01d96d116a9dbc76ebee57e67f26b2f6b4089a564b5",
-                        workload=3, tasksets=1_000_000, fetch_bytes=1312420519, write_bytes=343723776)
+MEASURED_TRAFFIC = dict(csrc_sha256="1d870b655533f69ae1d993db0ef08970a9b974ad1bf54a4c184a87cd48c12d60",
+                        workload=3, tasksets=1_000_000, fetch_bytes=1306717005, write_bytes=333333555)
 
 
 def csrc_sha256():
