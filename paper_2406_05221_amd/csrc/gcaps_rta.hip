@@ -177,9 +177,14 @@ int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mo
 int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                   uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
-  hipLaunchKernelGGL(fast::rta_screen_kernel, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy, wait_mode,
-                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
-                     deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+  if (wait_mode == GCAPS_WAIT_BUSY)
+    hipLaunchKernelGGL(fast::rta_screen_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                       deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+  else
+    hipLaunchKernelGGL(fast::rta_screen_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                       deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -385,7 +390,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
         (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
         (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
-        (const void *)fast::rta_screen_kernel,       (const void *)fast::rta_deep_kernel<true, 4>,
+        (const void *)fast::rta_screen_kernel<true>,   (const void *)fast::rta_screen_kernel<false>,       (const void *)fast::rta_deep_kernel<true, 4>,
         (const void *)fast::rta_deep_kernel<false, 4>,        (const void *)fast::rta_deep_kernel<true, 8>,
         (const void *)fast::rta_deep_kernel<false, 8>};
     bool raised = want > 65536;
