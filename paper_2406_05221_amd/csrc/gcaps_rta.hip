@@ -194,7 +194,7 @@ template <int TS>
 int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr, u32 blocks) {
   if constexpr (TS == 64) {
-    if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs)
+    if (kr <= (u32)fast::kCacheRanks && b->max_gseg <= (u32)fast::kCacheSegs && b->n_tasks <= 255)
         return launch_screen(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 4) return launch_fast_np<TS, 4>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
     if (kr <= 8) return launch_fast_np<TS, 8>(ctx, b, policy, wait_mode, d_resp, d_sched, kr, blocks);
