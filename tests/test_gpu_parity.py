@@ -267,3 +267,39 @@ def test_out_of_range_values_below_the_screened_ranks(oracle, gpu):
     batch["deadline_us"][rows[pick2], low[pick2]] = 2**24
     compare(oracle, B, ctx, batch)
     assert B.gcaps_last_wide_count(ctx) > 0
+
+
+def test_outputs_at_8_byte_alignment_only(oracle, gpu):
+    """Response buffers that are 8- but not 16-byte aligned (a view into a larger buffer), with
+    even and odd task counts: the kernels may use wider stores only where they are aligned."""
+    import torch
+    B, ctx, _ = gpu
+    for per_core in (5, 3):  # n = 20, n = 9
+        batch = relaxed_workload(1_111, seed=51, n_cores=4 if per_core == 5 else 3, per_core=per_core, S=3)
+        d = B.to_device(batch)
+        N, n = batch["cpu_us"].shape
+        want_r, want_s, _ = oracle.rta_batch(batch, BOTH, BUSY, threads=16)
+        for shift in (0, 1):
+            raw = torch.full((2 * N * n + 2,), -7, dtype=torch.int64, device="cuda:0")
+            d_resp = raw[shift:shift + 2 * N * n].view(2, N, n)
+            assert d_resp.data_ptr() % 16 == 8 * shift
+            d_sched = torch.full((2, N), 9, dtype=torch.uint8, device="cuda:0")
+            torch.cuda.synchronize()
+            B.gcaps_rta_batch_device(ctx, d, BOTH, BUSY, d_resp, d_sched)
+            B.gcaps_status(ctx)
+            assert (d_resp.cpu().numpy() == want_r).all() and (d_sched.cpu().numpy() == want_s).all()
+            assert (raw[:shift] == -7).all() and (raw[shift + 2 * N * n:] == -7).all()  # nothing outside the view
+
+
+def test_priorities_that_look_like_internal_marks(oracle, gpu):
+    """Any int32 is a legal priority.  Values around 2^30 (the first launch marks looked-up tasks
+    with such words in the priority column) and the extremes must not confuse anything."""
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(12)
+    batch = relaxed_workload(3_000, seed=61)
+    odd = rng.choice([2**30, 2**30 + 1, 2**30 + 2, 2**30 + 3, -(2**31), 2**31 - 1, 2**22, -(2**22) - 1],
+                     size=batch["prio"].shape)
+    hit = rng.random(batch["prio"].shape) < 0.05
+    batch["prio"] = np.where(hit, odd, batch["prio"]).astype(np.int32)
+    compare(oracle, B, ctx, batch)
+    assert B.gcaps_last_wide_count(ctx) > 0
