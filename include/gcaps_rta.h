@@ -92,6 +92,11 @@ enum {
  * Creates a context on device `device_id`.  `hip_stream` is a hipStream_t on
  * that device on which all work of the context is queued, or NULL for the
  * device's default stream; the stream stays owned by the caller.
+ *
+ * Tuning knobs are read from the environment here; results never depend on them:
+ *   GCAPS_SCREEN_TASKS    tasks per taskset that the first launch analyses (default 4)
+ *   GCAPS_DEEP_LANES      lanes per taskset in the second launch, 4 (default) or 8
+ *   GCAPS_CHUNK_TASKSETS  cap on the tasksets per internal chunk of a call
  */
 int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream);
 
