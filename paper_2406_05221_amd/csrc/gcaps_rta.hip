@@ -70,11 +70,9 @@ struct gcaps_ctx {
   DeviceBuffer status;       /* u32 first_bad, u32 wide_count */
   DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
   DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
-  DeviceBuffer deep_sorted;  /* the same list ordered by utilisation bucket (binning) */
-  DeviceBuffer deep_compact; /* the same list made contiguous (binning) */
+  DeviceBuffer deep_sorted;  /* the same list, contiguous and ordered (binning) */
+  DeviceBuffer deep_aux;     /* bucket and position inside the bucket of every list entry (binning) */
   u32 region_cap = 0;        /* slots per region of deep_list in the current chunk */
-  DeviceBuffer bin_keys;     /* bucket of every list entry */
-  DeviceBuffer bin_hist;     /* 256 bucket offsets + 256 scatter cursors */
   size_t lds_total = 65536;  /* LDS of one CU */
   DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
   DeviceBuffer staging_in, staging_out; /* device copies for the host entry point */
@@ -149,18 +147,27 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
       status[3] += status[1];
     }
     status[1] = 0; /* length of the list for the 64-bit kernel */
-    status[2] = 0; /* length of the compacted list for the second fast launch (binning only) */
+    status[2] = 0; /* length of the ordered list for the second fast launch (binning only) */
     status[4] = 0; /* next tile of the second fast launch */
   }
   status[fast::ST_DEEP_COUNTS + threadIdx.x] = 0; /* per-region lengths of the list for the second fast launch */
+  for (u32 k = threadIdx.x; k < fast::kOrderBuckets; k += blockDim.x) status[fast::ST_ORDER_HIST + k] = 0;
 }
 
 /* the list between the two fast launches: regions filled by the first launch, or (binning) the
  * contiguous list ordered by bucket */
 fast::ListSpec deep_list_spec(const gcaps_ctx *ctx, bool sorted) {
   u32 *status = (u32 *)ctx->status.ptr;
-  if (sorted) return fast::ListSpec{(u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u};
-  return fast::ListSpec{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap};
+  if (sorted)
+    return fast::ListSpec{(u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u, nullptr, nullptr, nullptr};
+  fast::ListSpec dl{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap,
+                    nullptr, nullptr, nullptr};
+  if (ctx->binning) {
+    dl.keys = (u32 *)ctx->deep_aux.ptr;
+    dl.positions = dl.keys + (size_t)ctx->region_cap * fast::kListRegions;
+    dl.hist = status + fast::ST_ORDER_HIST;
+  }
+  return dl;
 }
 
 template <int TS, int NP>
@@ -263,6 +270,8 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   const u32 producer_tiles = (N + 15u) / 16u; /* the narrowest tile width */
   ctx->region_cap = ((producer_tiles + fast::kListRegions - 1) / fast::kListRegions) * 64u;
   if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32));
+  if (rc == GCAPS_OK && ctx->binning)
+    rc = ctx->deep_aux.reserve((size_t)ctx->region_cap * fast::kListRegions * 2 * sizeof(u32));
   if (rc != GCAPS_OK) return rc;
 
   /* first launch: every taskset, the kr highest-priority tasks only */
@@ -274,28 +283,13 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
 
   /* second launch: the tasksets still alive, in full; persistent workgroups walk the list */
   if (kr < n && ctx->binning) {
-    /* counting sort of the list by utilisation bucket */
+    /* the list ordered by the bucket that the first launch gave every entry */
     rc = ctx->deep_sorted.reserve((size_t)N * sizeof(u32));
-    if (rc == GCAPS_OK) rc = ctx->bin_keys.reserve((size_t)N * sizeof(u32));
-    if (rc == GCAPS_OK) rc = ctx->bin_hist.reserve(2 * bin::kBuckets * sizeof(u32));
     if (rc != GCAPS_OK) return rc;
-    u32 *hist = (u32 *)ctx->bin_hist.ptr, *cursor = hist + bin::kBuckets;
     u32 *status = (u32 *)ctx->status.ptr;
-    const u32 *cnt = status + fast::ST_DEEP_TOTAL;
-    rc = ctx->deep_compact.reserve((size_t)N * sizeof(u32));
-    if (rc != GCAPS_OK) return rc;
-    u32 kb = (N + 63u) / 64u;
-    if (kb > (u32)ctx->n_cu * 16u) kb = (u32)ctx->n_cu * 16u;
-    hipLaunchKernelGGL(bin::compact_kernel, dim3(fast::kListRegions), dim3(256), 0, ctx->stream,
-                       (const u32 *)ctx->deep_list.ptr, (const u32 *)(status + fast::ST_DEEP_COUNTS),
-                       fast::kListRegions, ctx->region_cap, (u32 *)ctx->deep_compact.ptr, status + fast::ST_DEEP_TOTAL);
-    hipLaunchKernelGGL(bin::bin_clear_kernel, dim3(1), dim3(256), 0, ctx->stream, hist);
-    hipLaunchKernelGGL(bin::bin_key_kernel, dim3(kb), dim3(64), 0, ctx->stream, *b,
-                       (const u32 *)ctx->deep_compact.ptr, cnt, (u32 *)ctx->bin_keys.ptr, hist);
-    hipLaunchKernelGGL(bin::bin_scan_kernel, dim3(1), dim3(64), 0, ctx->stream, hist, cursor);
-    hipLaunchKernelGGL(bin::bin_scatter_kernel, dim3(kb), dim3(64), 0, ctx->stream,
-                       (const u32 *)ctx->deep_compact.ptr, cnt, (const u32 *)ctx->bin_keys.ptr, cursor,
-                       (u32 *)ctx->deep_sorted.ptr);
+    hipLaunchKernelGGL(bin::order_kernel, dim3(fast::kListRegions), dim3(256), 0, ctx->stream,
+                       deep_list_spec(ctx, false), (const u32 *)(status + fast::ST_ORDER_HIST),
+                       (u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL);
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
   if (kr < n) {
@@ -378,7 +372,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (rc == GCAPS_OK && hipGetDeviceProperties(&prop, device_id) != hipSuccess) rc = GCAPS_EDEVICE;
   if (rc == GCAPS_OK) {
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    rc = ctx->status.reserve(1024);
+    rc = ctx->status.reserve(fast::kStatusWords * sizeof(u32));
   }
   if (rc == GCAPS_OK) {
     /* the fast kernel's tiles live in dynamic LDS: raise the per-workgroup limit to what the CU has */
@@ -421,9 +415,7 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
   ctx->wide_list.release();
   ctx->deep_list.release();
   ctx->deep_sorted.release();
-  ctx->deep_compact.release();
-  ctx->bin_keys.release();
-  ctx->bin_hist.release();
+  ctx->deep_aux.release();
   ctx->staging_in.release();
   ctx->staging_out.release();
   if (ctx->host_status) (void)hipHostFree(ctx->host_status);
