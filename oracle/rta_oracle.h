@@ -53,6 +53,7 @@ extern "C" {
 #define ORACLE_OK 0
 #define ORACLE_EINVAL (-1) /* null pointer, zero sizes, unknown selector */
 #define ORACLE_ETASK (-2)  /* a task or parameter violates the task model */
+#define ORACLE_EORDER (-3) /* GPU priorities that disagree with the CPU priorities on one core (Sec. 4.3) */
 
 /*
  * One taskset.  Arrays are in caller order, any priority order.
@@ -94,6 +95,62 @@ int oracle_rta_batch(uint32_t n_tasksets, uint32_t n_tasks, uint32_t max_gseg,
                      const uint32_t *gm_us, const uint32_t *ge_us, int policy_mask, int wait_mode,
                      uint32_t options, int threads, int64_t *resp, uint8_t *sched,
                      uint64_t *terms_total, uint32_t *first_bad);
+
+/*
+ * Sec. 5.4: the GCAPS analysis of one taskset when the GPU segments of tau_i run at a
+ * priority gprio[i] of their own (larger = higher; equal values fall back to the CPU priority
+ * order).  Against oracle_rta_taskset with ORACLE_POLICY_GCAPS:
+ *   - the sums over higher-priority tasks of OTHER cores (second sums of Lemmas 10 and 13,
+ *     Lemma 11) run over the tasks with a higher GPU priority; hpp(tau_i) is unchanged;
+ *   - every release jitter is taken with D_h in place of R_h.
+ * The bounds of different tasks then do not depend on each other: every task is analysed,
+ * resp[i] = R_i or ORACLE_RESP_MISS, *sched = 1 iff none missed.  theta and L play no part.
+ * Returns ORACLE_EORDER when two tasks of one core are ordered differently by prio and gprio.
+ */
+int oracle_gprio_rta_taskset(uint32_t n_tasks, uint32_t max_gseg, uint32_t eps_us,
+                             const uint32_t *cpu_us, const uint32_t *period_us,
+                             const uint32_t *deadline_us, const int32_t *prio, const uint8_t *core,
+                             const uint8_t *n_gseg, const uint32_t *gm_us, const uint32_t *ge_us,
+                             const int32_t *gprio, int wait_mode, uint32_t options, int64_t *resp,
+                             uint8_t *sched, uint64_t *terms);
+
+/*
+ * Sec. 4.3: search for GPU-segment priorities by Audsley's scheme.  Levels are handed out
+ * from the lowest (1) to the highest (n).  At each level the unassigned tasks are tried from
+ * the lowest to the highest CPU priority; a task is a candidate only if no unassigned task of
+ * its core has a lower CPU priority (the two orders must agree on a core); the first candidate
+ * whose bound of Sec. 5.4 - with every other unassigned task above it - meets its deadline
+ * takes the level.  The search fails when a level finds no task, or (checked first) when some
+ * task's own demand C_i + G_i + 2*eps*eta_i + (eta_i + 1)*eps exceeds D_i.
+ * Outputs (caller order): success: gprio[i] = level of tau_i, resp[i] = its bound at that
+ * level, *sched = 1; failure: gprio[i] = 0, resp[i] = ORACLE_RESP_NOT_ANALYSED, *sched = 0.
+ *
+ * Pins: the taskset of Table 2 (printed: fails with GPU = CPU priorities, passes with tau_4
+ * above tau_3; hand-worked bounds), agreement with oracle_rta_taskset where Sec. 5.4 changes
+ * nothing, an exhaustive search over all admissible priority orders of small tasksets
+ * (Audsley's scheme finds an order iff one exists), and the discrete-event simulator run
+ * with the assigned GPU priorities.
+ */
+int oracle_gprio_assign_taskset(uint32_t n_tasks, uint32_t max_gseg, uint32_t eps_us,
+                                const uint32_t *cpu_us, const uint32_t *period_us,
+                                const uint32_t *deadline_us, const int32_t *prio, const uint8_t *core,
+                                const uint8_t *n_gseg, const uint32_t *gm_us, const uint32_t *ge_us,
+                                int wait_mode, uint32_t options, int32_t *gprio, int64_t *resp,
+                                uint8_t *sched, uint64_t *terms);
+
+/*
+ * The search for every taskset of a batch (layout as oracle_rta_batch; gprio and resp are
+ * [n_tasksets*n_tasks], sched [n_tasksets]).  skip (may be NULL): tasksets with skip[s] != 0
+ * are not searched (they passed the test with GPU = CPU priorities): gprio = 0, resp =
+ * ORACLE_RESP_NOT_ANALYSED, sched = 1.
+ */
+int oracle_gprio_assign_batch(uint32_t n_tasksets, uint32_t n_tasks, uint32_t max_gseg,
+                              const uint32_t *eps_us, const uint32_t *cpu_us, const uint32_t *period_us,
+                              const uint32_t *deadline_us, const int32_t *prio, const uint8_t *core,
+                              const uint8_t *n_gseg, const uint32_t *gm_us, const uint32_t *ge_us,
+                              const uint8_t *skip, int wait_mode, uint32_t options, int threads,
+                              int32_t *gprio, int64_t *resp, uint8_t *sched, uint64_t *terms_total,
+                              uint32_t *first_bad);
 
 #ifdef __cplusplus
 }

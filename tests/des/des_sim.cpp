@@ -42,7 +42,7 @@ struct Op {
 };
 
 struct TaskDef {
-  int core, prio, T, D, offset, eta;
+  int core, prio, gprio, T, D, offset, eta; /* gprio: priority of the GPU segments (Sec. 4.3) */
   std::vector<int> c;      /* eta + 1 CPU segments */
   std::vector<int> gm, ge; /* eta GPU segments */
 };
@@ -80,6 +80,8 @@ struct Sim {
   bool overrun = false;
 
   bool higher(int a, int b) const { return def[a].prio > def[b].prio; }
+  /* the runlist decisions of Alg. 1 compare GPU-segment priorities (end of Sec. 4.3) */
+  bool higher_g(int a, int b) const { return def[a].gprio > def[b].gprio; }
 
   void build_program(int i) {
     const TaskDef &d = def[i];
@@ -97,11 +99,11 @@ struct Sim {
   }
 
   /* Alg. 1, add branch.  Returns true when the running set changes. */
-  bool add_changes(int i) const { return running < 0 || higher(i, running); }
+  bool add_changes(int i) const { return running < 0 || higher_g(i, running); }
   void apply_add(int i) {
     if (running < 0) {
       running = i;
-    } else if (higher(i, running)) {
+    } else if (higher_g(i, running)) {
       pending[running] = 1;
       running = i;
     } else {
@@ -114,7 +116,7 @@ struct Sim {
     if (running == i) {
       int k = -1;
       for (int x = 0; x < n; ++x)
-        if (pending[x] && (k < 0 || higher(x, k))) k = x;
+        if (pending[x] && (k < 0 || higher_g(x, k))) k = x;
       running = k;
       if (k >= 0) pending[k] = 0;
     } else {
@@ -311,11 +313,13 @@ struct Sim {
  * the jobs of task i that completed within `horizon` ticks, jobs_done[i] their
  * number.  Returns 0, or 1 when a job was released while its predecessor was
  * still running (the simulation stops there), or -1 on bad arguments.
+ * gprio (may be null: same as prio): priorities of the GPU segments, used by the runlist
+ * decisions of the GCAPS policy only.
  */
-extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
-                       const int *core, const int *prio, const int *T, const int *D,
-                       const int *offset, const int *eta, const int *c, const int *gm,
-                       const int *ge, int horizon, int *max_resp, int *jobs_done) {
+extern "C" int des_run_gprio(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
+                             const int *core, const int *prio, const int *gprio, const int *T, const int *D,
+                             const int *offset, const int *eta, const int *c, const int *gm,
+                             const int *ge, int horizon, int *max_resp, int *jobs_done) {
   if (n <= 0 || n > 16 || max_eta < 0 || L <= 0 || (policy != 1 && policy != 2) ||
       (wait_mode != 0 && wait_mode != 1))
     return -1;
@@ -333,6 +337,7 @@ extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta,
     TaskDef &d = sim.def[i];
     d.core = core[i];
     d.prio = prio[i];
+    d.gprio = gprio ? gprio[i] : prio[i];
     d.T = T[i];
     d.D = D[i];
     d.offset = offset[i];
@@ -355,4 +360,12 @@ extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta,
     jobs_done[i] = sim.st[i].jobs_done;
   }
   return sim.overrun ? 1 : 0;
+}
+
+extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
+                       const int *core, const int *prio, const int *T, const int *D,
+                       const int *offset, const int *eta, const int *c, const int *gm,
+                       const int *ge, int horizon, int *max_resp, int *jobs_done) {
+  return des_run_gprio(n, max_eta, policy, wait_mode, theta, eps, L, core, prio, nullptr, T, D, offset, eta, c,
+                       gm, ge, horizon, max_resp, jobs_done);
 }

@@ -24,11 +24,13 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.des_run.restype = ctypes.c_int
+        _lib.des_run_gprio.restype = ctypes.c_int
     return _lib
 
 
-def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon):
+def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon, gprio=None):
     """tasks: list of dicts with core, prio, T, D, c (eta+1 ints), gm, ge (eta ints each).
+    gprio: priorities of the GPU segments (GCAPS runlist decisions), default = prio.
     Returns (rc, max_resp[n], jobs_done[n])."""
     n = len(tasks)
     max_eta = max(len(t["ge"]) for t in tasks)
@@ -54,6 +56,8 @@ def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon):
     mr = np.zeros(n, np.int32)
     jd = np.zeros(n, np.int32)
     p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
-    rc = _load().des_run(n, max_eta, policy, wait_mode, theta, eps, L, p(core), p(prio), p(T), p(D),
-                         p(off), p(eta), p(c), p(gm), p(ge), horizon, p(mr), p(jd))
+    gp = prio if gprio is None else np.ascontiguousarray(gprio, dtype=np.int32)
+    assert gp.size == n
+    rc = _load().des_run_gprio(n, max_eta, policy, wait_mode, theta, eps, L, p(core), p(prio), p(gp), p(T),
+                               p(D), p(off), p(eta), p(c), p(gm), p(ge), horizon, p(mr), p(jd))
     return rc, mr, jd

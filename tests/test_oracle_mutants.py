@@ -9,6 +9,7 @@ import types
 import pytest
 
 import test_oracle_des as des_tests
+import test_oracle_gprio as gprio_tests
 import test_oracle_pins as pin_tests
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -44,6 +45,37 @@ MUTANTS = {
                                  "bool same_core(size_t h, size_t i) const { return tau[h].core != tau[i].core; }"),
     "priority_order_reversed": ("return prio[a] > prio[b]; });", "return prio[a] < prio[b]; });"),
     "G_i_without_Gm": ("t.G = t.Gm + t.Ge;", "t.G = t.Ge;"),
+    "gprio_jitter_Jg_dropped": ("i64 jitter_g(size_t h) const { return tau[h].D - tau[h].Ge; }",
+                                "i64 jitter_g(size_t h) const { (void)h; return 0; }"),
+    "gprio_jitter_Jg_from_deadline_only": ("i64 jitter_g(size_t h) const { return tau[h].D - tau[h].Ge; }",
+                                           "i64 jitter_g(size_t h) const { return tau[h].D; }"),
+    "gprio_jitter_Jc_from_deadline_only": (
+        "i64 jitter_c(size_t h) const { return tau[h].D - (tau[h].C + tau[h].Gm); }",
+        "i64 jitter_c(size_t h) const { return tau[h].D; }"),
+    "gprio_lemma11_dropped": ("      /* Lemma 10, second sum (eta^g_i > 0); Lemma 11 (eta^g_i = 0) */\n      for (size_t h = 0; h < n; ++h)\n        if (higher_g[h] &&",
+                              "      for (size_t h = 0; h < n; ++h)\n        if (uses_gpu(i) && higher_g[h] &&"),
+    "gprio_jitter_Jc_dropped": ("i64 jitter_c(size_t h) const { return tau[h].D - (tau[h].C + tau[h].Gm); }",
+                                "i64 jitter_c(size_t h) const { (void)h; return 0; }"),
+    "gprio_Ge_star_without_updates": ("i64 ge_star(size_t h) const { return add(tau[h].Ge, updates(h)); }",
+                                      "i64 ge_star(size_t h) const { return tau[h].Ge; }"),
+    "gprio_lemma13_same_core_with_updates": (
+        "if (on_core_of(i, h) && uses_gpu(h)) s = add(s, arrivals_times(R + jitter_g(h), h, tau[h].Ge));",
+        "if (on_core_of(i, h) && uses_gpu(h)) s = add(s, arrivals_times(R + jitter_g(h), h, ge_star(h)));"),
+    "gprio_lemma13_for_cpu_only_tasks_too": ("      if (uses_gpu(i)) {", "      if (true) {"),
+    "gprio_blocking_dropped": (
+        "return add(add(add(tau[i].C, tau[i].G), updates(i)), mul(tau[i].eta + 1, p.eps));",
+        "return add(add(tau[i].C, tau[i].G), updates(i));"),
+    "gprio_same_core_taken_as_other_cores": (
+        "bool on_core_of(size_t i, size_t h) const { return tau[h].core == tau[i].core; }",
+        "bool on_core_of(size_t i, size_t h) const { return tau[h].core != tau[i].core; }"),
+    "gprio_solve_stops_early": ("      if (next == R) break;\n      R = next;", "      R = next;\n      break;"),
+    "search_tries_highest_cpu_priority_first": ("for (size_t k = n_tasks; k-- > 0 && !placed;) {",
+                                                "for (size_t k = 0; k < n_tasks && !placed; ++k) {"),
+    "search_ignores_the_same_core_order": ("if (unassigned[m] && tau[m].core == tau[k].core) feasible = false;",
+                                           "if (false) feasible = false;"),
+    "search_levels_from_the_top": ("level_of[k] = (int32_t)level;", "level_of[k] = (int32_t)(n_tasks + 1 - level);"),
+    "search_puts_assigned_tasks_above": ("      std::vector<char> higher_g(unassigned);\n      higher_g[k] = 0;",
+                                         "      std::vector<char> higher_g(n_tasks, 1);"),
     "stops_one_iteration_early": ("      } else if (next == R) {\n        break;",
                                   "      } else if (next == R || true) {\n        break;"),
 }
@@ -65,6 +97,15 @@ PINS = [
     des_tests.test_directed_carry_in_other_core,
     des_tests.test_directed_self_suspension_same_core,
     lambda o: [des_tests.test_simulated_response_never_exceeds_bound(o, p, w) for p, w in pin_tests.VARIANTS],
+    gprio_tests.test_table2_printed_verdicts,
+    gprio_tests.test_table2_hand_worked_values,
+    gprio_tests.test_runlist_update_cost_hand_worked,
+    gprio_tests.test_same_core_self_suspension_with_update_cost_hand_worked,
+    gprio_tests.test_carry_in_jitter_is_deadline_minus_gpu_time,
+    gprio_tests.test_search_prefers_the_lowest_cpu_priority_candidate,
+    lambda o: [gprio_tests.test_search_finds_an_order_iff_one_exists(o, w) for w in (0, 1)],
+    lambda o: [gprio_tests.test_simulated_response_never_exceeds_bound_under_separate_priorities(o, w)
+               for w in (0, 1)],
 ]
 
 
@@ -72,6 +113,8 @@ def mutant_module(oracle, lib):
     m = types.SimpleNamespace(**{k: getattr(oracle, k) for k in dir(oracle) if k.isupper()})
     m.OracleError = oracle.OracleError
     m.rta_taskset = lambda *a, **kw: oracle.rta_taskset(*a, lib=lib, **kw)
+    m.gprio_rta_taskset = lambda *a, **kw: oracle.gprio_rta_taskset(*a, lib=lib, **kw)
+    m.gprio_assign_taskset = lambda *a, **kw: oracle.gprio_assign_taskset(*a, lib=lib, **kw)
     return m
 
 
