@@ -132,8 +132,8 @@ int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy,
                            int64_t *d_out_resp, uint8_t *d_out_sched);
 
 /*
- * Waits for the context's stream and reports on the most recent
- * gcaps_rta_batch_device call: GCAPS_OK, or GCAPS_ETASK with the smallest
+ * Waits for the context's stream and reports on the most recent device-resident
+ * call (gcaps_rta_batch_device, gcaps_gprio_assign_batch_device): GCAPS_OK, or GCAPS_ETASK with the smallest
  * invalid taskset index in *first_bad_taskset (may be NULL), or GCAPS_EDEVICE.
  */
 int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset);
@@ -145,6 +145,45 @@ int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset);
  * instead.  Results are exact on both routes; the count only explains speed.
  */
 int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count);
+
+/*
+ * GPU-segment priority assignment (Sec. 4.3) with the analysis of Sec. 5.4, under GCAPS.
+ *
+ * For every taskset of the batch the library searches GPU-segment priorities pi^g_i by
+ * Audsley's scheme: levels are handed out from the lowest (1) to the highest (n); at each
+ * level the tasks without a level yet are tried from the lowest to the highest CPU priority
+ * (`prio`); a task is a candidate only if no such task of its core has a lower CPU priority
+ * (on a core the GPU order must agree with the CPU order, or the taskset may deadlock); the
+ * first candidate whose response-time bound meets its deadline takes the level.  The bound
+ * of a candidate is that of Sec. 5.3 with the changes of Sec. 5.4: the sums over
+ * higher-priority tasks of OTHER cores (second sums of Lemmas 10 and 13, Lemma 11) run over
+ * the tasks that would be above it on the GPU, i.e. every other task without a level; the
+ * same-core sums are unchanged; every release jitter uses D_h in place of R_h.  The search
+ * fails when a level finds no task, or when some task's own demand
+ * C_i + G_i + 2*eps*eta^g_i + (eta^g_i + 1)*eps exceeds D_i (it then passes at no level).
+ * theta_us and slice_us of the batch are not read (may be NULL here).
+ *
+ *   wait_mode  GCAPS_WAIT_BUSY or GCAPS_WAIT_SUSPEND
+ *   skip       uint8 [n_tasksets] or NULL: tasksets with skip[s] != 0 are not searched
+ *              (typically out_sched of the GCAPS analysis: Sec. 6.1 tries separate
+ *              priorities only for tasksets that fail with pi^g = pi^c)
+ *   out_gprio  int32 [n_tasksets][n_tasks], caller order: level of tau_i, larger = higher
+ *              GPU priority; 0 for every task of a taskset that failed or was skipped
+ *   out_resp   int64 [n_tasksets][n_tasks]: the bound of tau_i at its level;
+ *              GCAPS_RESP_NOT_ANALYSED for a taskset that failed or was skipped
+ *   out_sched  uint8 [n_tasksets]: 1 = an assignment was found, or skipped; 0 = none exists
+ *
+ * gcaps_gprio_assign_batch takes HOST pointers and returns when the results are in place
+ * (errors as gcaps_rta_batch); gcaps_gprio_assign_batch_device takes DEVICE pointers, queues
+ * the work on the context's stream and returns (errors as gcaps_rta_batch_device;
+ * gcaps_status and gcaps_last_wide_count report on it likewise).
+ */
+int gcaps_gprio_assign_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode, const uint8_t *skip,
+                             int32_t *out_gprio, int64_t *out_resp, uint8_t *out_sched,
+                             uint32_t *first_bad_taskset);
+int gcaps_gprio_assign_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode,
+                                    const uint8_t *d_skip, int32_t *d_out_gprio, int64_t *d_out_resp,
+                                    uint8_t *d_out_sched);
 
 /*
  * Optional ordering (off by default) of the tasksets that need the second,

@@ -24,7 +24,8 @@ GCAPS_OK, GCAPS_EINVAL, GCAPS_ETASK, GCAPS_ENOMEM, GCAPS_EDEVICE = 0, -1, -2, -3
 GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
-           "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror"]
+           "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
+           "gcaps_gprio_assign_batch_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -50,6 +51,10 @@ _lib.gcaps_last_wide_count.restype = _int
 _lib.gcaps_last_wide_count.argtypes = [_p, ctypes.POINTER(_u32)]
 _lib.gcaps_set_binning.restype = _int
 _lib.gcaps_set_binning.argtypes = [_p, _int]
+_lib.gcaps_gprio_assign_batch.restype = _int
+_lib.gcaps_gprio_assign_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p, ctypes.POINTER(_u32)]
+_lib.gcaps_gprio_assign_batch_device.restype = _int
+_lib.gcaps_gprio_assign_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p]
 _lib.gcaps_strerror.restype = ctypes.c_char_p
 _lib.gcaps_strerror.argtypes = [_int]
 
@@ -169,3 +174,49 @@ def gcaps_last_wide_count(ctx):
     if rc != GCAPS_OK:
         raise GcapsError(rc)
     return c.value
+
+
+def gcaps_gprio_assign_batch(ctx, batch, wait_mode, skip=None):
+    """Host entry point of the GPU-segment priority assignment.  batch: dict of numpy arrays;
+    skip: uint8 [N] or None.  Returns (gprio int32 [N, n], resp int64 [N, n], sched uint8 [N])."""
+    N, n, S = _shape(batch)
+    keep = {}
+    b = gcaps_batch(n_tasksets=N, n_tasks=n, max_gseg=S)
+    for name, dtype, ndim in _FIELDS:
+        a = np.ascontiguousarray(batch[name], dtype=dtype)
+        assert a.ndim == ndim and a.shape[0] == N, name
+        keep[name] = a
+        setattr(b, name, a.ctypes.data if a.size else None)
+    sk = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
+    assert sk is None or sk.shape == (N,)
+    gprio = np.empty((N, n), np.int32)
+    resp = np.empty((N, n), np.int64)
+    sched = np.empty(N, np.uint8)
+    bad = _u32(0xFFFFFFFF)
+    rc = _lib.gcaps_gprio_assign_batch(ctx, ctypes.byref(b), wait_mode, sk.ctypes.data if sk is not None else None,
+                                       gprio.ctypes.data, resp.ctypes.data, sched.ctypes.data, ctypes.byref(bad))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)
+    return gprio, resp, sched
+
+
+def gcaps_gprio_assign_batch_device(ctx, dbatch, wait_mode, d_skip, d_gprio, d_resp, d_sched):
+    """Device entry point of the GPU-segment priority assignment.  dbatch as for
+    ``gcaps_rta_batch_device``; d_skip: uint8 [N] device tensor or None; d_gprio: int32 [N, n],
+    d_resp: int64 [N, n], d_sched: uint8 [N] device tensors.  Queues the work and returns."""
+    N, n = dbatch["cpu_us"].shape
+    S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
+    b = gcaps_batch(n_tasksets=int(N), n_tasks=int(n), max_gseg=int(S))
+    for name, _, _ in _FIELDS:
+        t = dbatch[name]
+        assert t.is_cuda and t.is_contiguous(), name
+        setattr(b, name, t.data_ptr() if t.numel() else None)
+    for t, count, size in ((d_gprio, N * n, 4), (d_resp, N * n, 8), (d_sched, N, 1)):
+        assert t.is_cuda and t.is_contiguous() and t.numel() == count and t.element_size() == size
+    if d_skip is not None:
+        assert d_skip.is_cuda and d_skip.is_contiguous() and d_skip.numel() == N and d_skip.element_size() == 1
+    rc = _lib.gcaps_gprio_assign_batch_device(ctx, ctypes.byref(b), wait_mode,
+                                              d_skip.data_ptr() if d_skip is not None else None,
+                                              d_gprio.data_ptr(), d_resp.data_ptr(), d_sched.data_ptr())
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)

@@ -18,6 +18,7 @@
 #include "rta_fast.hip.inc"
 #include "rta_deep.hip.inc"
 #include "rta_bin.hip.inc"
+#include "gprio_wide.hip.inc"
 
 namespace {
 
@@ -113,23 +114,30 @@ u32 wide_slots(const gcaps_ctx *ctx, u32 n_tasksets) {
   return want < cap ? want : cap;
 }
 
-int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
-                uint8_t *d_sched, const u32 *d_list, const u32 *d_list_count, u32 max_items) {
-  const u32 slots = wide_slots(ctx, max_items);
-  const size_t col = (size_t)slots * b->n_tasks;
+/* the per-lane scratch columns of the one-lane-per-taskset kernels, for `slots` lanes */
+int wide_columns(gcaps_ctx *ctx, u32 n_tasks, u32 slots, wide::Scratch *ws) {
+  const size_t col = (size_t)slots * n_tasks;
   const size_t bytes = col * (4 * sizeof(u32) + 3 * sizeof(u64));
   int rc = ctx->wide_scratch.reserve(bytes);
   if (rc != GCAPS_OK) return rc;
   char *base = (char *)ctx->wide_scratch.ptr;
+  ws->CGm = (u64 *)base;
+  ws->Ge = ws->CGm + col;
+  ws->K = ws->Ge + col;
+  ws->T = (u32 *)(ws->K + col);
+  ws->D = ws->T + col;
+  ws->meta = ws->D + col;
+  ws->R = ws->meta + col;
+  ws->n_slots = slots;
+  return GCAPS_OK;
+}
+
+int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                uint8_t *d_sched, const u32 *d_list, const u32 *d_list_count, u32 max_items) {
+  const u32 slots = wide_slots(ctx, max_items);
   wide::Scratch ws;
-  ws.CGm = (u64 *)base;
-  ws.Ge = ws.CGm + col;
-  ws.K = ws.Ge + col;
-  ws.T = (u32 *)(ws.K + col);
-  ws.D = ws.T + col;
-  ws.meta = ws.D + col;
-  ws.R = ws.meta + col;
-  ws.n_slots = slots;
+  int rc = wide_columns(ctx, b->n_tasks, slots, &ws);
+  if (rc != GCAPS_OK) return rc;
   hipLaunchKernelGGL(wide::rta_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, policy,
                      wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count,
                      ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
@@ -303,9 +311,10 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
 }
 
 /* Splits a call into chunks of tasksets small enough for the kernels' 32-bit byte offsets:
- * within a chunk every input array and each policy's block of responses stays below 4 GiB. */
-int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
-               uint8_t *d_sched) {
+ * within a chunk every input array and each block of responses stays below 4 GiB.
+ * run(sub-batch, first taskset of the chunk) is called per chunk. */
+template <class F>
+int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
   const u64 n = b->n_tasks, S = b->max_gseg ? b->max_gseg : 1, N = b->n_tasksets;
   u64 chunk = (1ull << 28) / n;                 /* 8-byte responses: N*n*8 < 2^31 */
   const u64 by_seg = (1ull << 30) / (n * S);    /* 4-byte segments:  N*n*S*4 < 2^32 */
@@ -313,16 +322,14 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
   if (ctx->chunk_cap && ctx->chunk_cap < chunk) chunk = ctx->chunk_cap;
   if (chunk > 64) chunk &= ~63ull;
   if (chunk < 1) chunk = 1;
-  ctx->resp_stride = (size_t)(N * n);
-  ctx->sched_stride = (size_t)N;
   ctx->last_n_tasksets = b->n_tasksets;
   for (u64 c0 = 0; c0 < N; c0 += chunk) {
     gcaps_batch sub = *b;
     const u64 cn = N - c0 < chunk ? N - c0 : chunk;
     sub.n_tasksets = (u32)cn;
-    sub.theta_us += c0;
+    if (sub.theta_us) sub.theta_us += c0;
     sub.eps_us += c0;
-    sub.slice_us += c0;
+    if (sub.slice_us) sub.slice_us += c0;
     sub.cpu_us += c0 * n;
     sub.period_us += c0 * n;
     sub.deadline_us += c0 * n;
@@ -333,9 +340,99 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
     if (sub.gm_us) sub.gm_us += c0 * n * b->max_gseg;
     if (sub.ge_us) sub.ge_us += c0 * n * b->max_gseg;
     ctx->ts_offset = (u32)c0;
-    const int rc = run_chunk(ctx, &sub, policy, wait_mode, d_resp + c0 * n, d_sched + c0, c0 == 0);
+    const int rc = run(&sub, c0);
     if (rc != GCAPS_OK) return rc;
   }
+  return GCAPS_OK;
+}
+
+int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+               uint8_t *d_sched) {
+  const u64 n = b->n_tasks, N = b->n_tasksets;
+  ctx->resp_stride = (size_t)(N * n);
+  ctx->sched_stride = (size_t)N;
+  return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
+    return run_chunk(ctx, sub, policy, wait_mode, d_resp + c0 * n, d_sched + c0, c0 == 0);
+  });
+}
+
+/* GPU-segment priority assignment of one chunk */
+int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const uint8_t *d_skip, int32_t *d_gprio,
+                    int64_t *d_resp, uint8_t *d_sched, bool first_chunk) {
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr,
+                     first_chunk ? 1 : 0);
+  if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+  const u32 N = b->n_tasksets;
+  ctx->wide_only = true;
+  const u32 slots = wide_slots(ctx, N);
+  wide::Scratch ws;
+  int rc = wide_columns(ctx, b->n_tasks, slots, &ws);
+  if (rc != GCAPS_OK) return rc;
+  hipLaunchKernelGGL(gprio::gprio_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, wait_mode, d_skip,
+                     (int *)d_gprio, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, (const u32 *)nullptr,
+                     (const u32 *)nullptr, ctx->ts_offset);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+int run_gprio(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const uint8_t *d_skip, int32_t *d_gprio,
+              int64_t *d_resp, uint8_t *d_sched) {
+  const u64 n = b->n_tasks;
+  return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
+    return run_gprio_chunk(ctx, sub, wait_mode, d_skip ? d_skip + c0 : nullptr, d_gprio + c0 * n, d_resp + c0 * n,
+                           d_sched + c0, c0 == 0);
+  });
+}
+
+int check_gprio_batch(const gcaps_batch *b, int wait_mode, const void *gprio, const void *resp, const void *sched) {
+  if (!b || !gprio || !resp || !sched) return GCAPS_EINVAL;
+  if (b->n_tasksets == 0 || b->n_tasks == 0 || b->n_tasks > 255 || b->max_gseg > 255) return GCAPS_EINVAL;
+  if (!b->eps_us || !b->cpu_us || !b->period_us || !b->deadline_us || !b->prio || !b->core || !b->n_gseg)
+    return GCAPS_EINVAL;
+  if (b->max_gseg > 0 && (!b->gm_us || !b->ge_us)) return GCAPS_EINVAL;
+  if (wait_mode != GCAPS_WAIT_BUSY && wait_mode != GCAPS_WAIT_SUSPEND) return GCAPS_EINVAL;
+  return GCAPS_OK;
+}
+
+/* Device copy of a host batch in the context's staging buffer (one allocation, every array
+ * aligned to 256 bytes), queued on the context's stream.  skip (may be null): one more
+ * per-taskset byte array, its device copy in *d_skip. */
+int upload_batch(gcaps_ctx *ctx, const gcaps_batch *batch, gcaps_batch *dev, const uint8_t *skip,
+                 const uint8_t **d_skip) {
+  const size_t N = batch->n_tasksets, n = batch->n_tasks, S = batch->max_gseg;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t sz_ts = up(N * 4), sz_task4 = up(N * n * 4), sz_task1 = up(N * n), sz_seg = up(N * n * S * 4);
+  const size_t in_bytes = 3 * sz_ts + 4 * sz_task4 + 2 * sz_task1 + 2 * sz_seg + up(N);
+  int rc = ctx->staging_in.reserve(in_bytes);
+  if (rc != GCAPS_OK) return rc;
+  char *cur = (char *)ctx->staging_in.ptr;
+  bool ok = true;
+  auto put = [&](const void *src, size_t bytes, size_t reserved) -> const void * {
+    void *dst = cur;
+    cur += reserved;
+    if (!src) return nullptr;
+    if (bytes && hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) ok = false;
+    return dst;
+  };
+  gcaps_batch d = *batch;
+  d.theta_us = (const u32 *)put(batch->theta_us, N * 4, sz_ts);
+  d.eps_us = (const u32 *)put(batch->eps_us, N * 4, sz_ts);
+  d.slice_us = (const u32 *)put(batch->slice_us, N * 4, sz_ts);
+  d.cpu_us = (const u32 *)put(batch->cpu_us, N * n * 4, sz_task4);
+  d.period_us = (const u32 *)put(batch->period_us, N * n * 4, sz_task4);
+  d.deadline_us = (const u32 *)put(batch->deadline_us, N * n * 4, sz_task4);
+  d.prio = (const int32_t *)put(batch->prio, N * n * 4, sz_task4);
+  d.core = (const uint8_t *)put(batch->core, N * n, sz_task1);
+  d.n_gseg = (const uint8_t *)put(batch->n_gseg, N * n, sz_task1);
+  d.n_cseg = nullptr;
+  d.gm_us = S ? (const u32 *)put(batch->gm_us, N * n * S * 4, sz_seg) : nullptr;
+  d.ge_us = S ? (const u32 *)put(batch->ge_us, N * n * S * 4, sz_seg) : nullptr;
+  const uint8_t *ds = (const uint8_t *)put(skip, N, up(N));
+  if (d_skip) *d_skip = ds;
+  if (!ok) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  *dev = d;
   return GCAPS_OK;
 }
 
@@ -477,42 +574,14 @@ extern "C" int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int pol
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
 
-  const size_t N = batch->n_tasksets, n = batch->n_tasks, S = batch->max_gseg;
+  const size_t N = batch->n_tasksets, n = batch->n_tasks;
   const size_t P = (size_t)npol(policy);
-  /* one staging allocation, every array aligned to 256 bytes */
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
-  const size_t sz_ts = up(N * 4), sz_task4 = up(N * n * 4), sz_task1 = up(N * n), sz_seg = up(N * n * S * 4);
-  const size_t in_bytes = 3 * sz_ts + 4 * sz_task4 + 2 * sz_task1 + 2 * sz_seg;
   const size_t resp_bytes = up(P * N * n * 8), sched_bytes = up(P * N);
-  rc = ctx->staging_in.reserve(in_bytes);
+  gcaps_batch d;
+  rc = upload_batch(ctx, batch, &d, nullptr, nullptr);
   if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(resp_bytes + sched_bytes);
   if (rc != GCAPS_OK) return rc;
-
-  char *cur = (char *)ctx->staging_in.ptr;
-  bool ok = true;
-  auto put = [&](const void *src, size_t bytes, size_t reserved) -> const void * {
-    void *dst = cur;
-    cur += reserved;
-    if (bytes && hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) ok = false;
-    return dst;
-  };
-  gcaps_batch d = *batch;
-  d.theta_us = (const u32 *)put(batch->theta_us, N * 4, sz_ts);
-  d.eps_us = (const u32 *)put(batch->eps_us, N * 4, sz_ts);
-  d.slice_us = (const u32 *)put(batch->slice_us, N * 4, sz_ts);
-  d.cpu_us = (const u32 *)put(batch->cpu_us, N * n * 4, sz_task4);
-  d.period_us = (const u32 *)put(batch->period_us, N * n * 4, sz_task4);
-  d.deadline_us = (const u32 *)put(batch->deadline_us, N * n * 4, sz_task4);
-  d.prio = (const int32_t *)put(batch->prio, N * n * 4, sz_task4);
-  d.core = (const uint8_t *)put(batch->core, N * n, sz_task1);
-  d.n_gseg = (const uint8_t *)put(batch->n_gseg, N * n, sz_task1);
-  d.n_cseg = nullptr;
-  d.gm_us = S ? (const u32 *)put(batch->gm_us, N * n * S * 4, sz_seg) : nullptr;
-  d.ge_us = S ? (const u32 *)put(batch->ge_us, N * n * S * 4, sz_seg) : nullptr;
-  if (!ok) {
-    (void)hipGetLastError();
-    return GCAPS_EDEVICE;
-  }
   int64_t *d_resp = (int64_t *)ctx->staging_out.ptr;
   uint8_t *d_sched = (uint8_t *)ctx->staging_out.ptr + resp_bytes;
   rc = run_device(ctx, &d, policy, wait_mode, d_resp, d_sched);
@@ -521,6 +590,50 @@ extern "C" int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int pol
   if (rc != GCAPS_OK) return rc;
   if (hipMemcpyAsync(out_resp, d_resp, P * N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
       hipMemcpyAsync(out_sched, d_sched, P * N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_gprio_assign_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode,
+                                               const uint8_t *d_skip, int32_t *d_out_gprio, int64_t *d_out_resp,
+                                               uint8_t *d_out_sched) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_gprio_batch(batch, wait_mode, d_out_gprio, d_out_resp, d_out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  return run_gprio(ctx, batch, wait_mode, d_skip, d_out_gprio, d_out_resp, d_out_sched);
+}
+
+extern "C" int gcaps_gprio_assign_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode,
+                                        const uint8_t *skip, int32_t *out_gprio, int64_t *out_resp,
+                                        uint8_t *out_sched, uint32_t *first_bad_taskset) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_gprio_batch(batch, wait_mode, out_gprio, out_resp, out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  const size_t N = batch->n_tasksets, n = batch->n_tasks;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t resp_bytes = up(N * n * 8), gprio_bytes = up(N * n * 4), sched_bytes = up(N);
+  gcaps_batch d;
+  const uint8_t *d_skip = nullptr;
+  rc = upload_batch(ctx, batch, &d, skip, &d_skip);
+  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(resp_bytes + gprio_bytes + sched_bytes);
+  if (rc != GCAPS_OK) return rc;
+  int64_t *d_resp = (int64_t *)ctx->staging_out.ptr;
+  int32_t *d_gprio = (int32_t *)((char *)ctx->staging_out.ptr + resp_bytes);
+  uint8_t *d_sched = (uint8_t *)ctx->staging_out.ptr + resp_bytes + gprio_bytes;
+  rc = run_gprio(ctx, &d, wait_mode, d_skip, d_gprio, d_resp, d_sched);
+  if (rc != GCAPS_OK) return rc;
+  rc = gcaps_status(ctx, first_bad_taskset);
+  if (rc != GCAPS_OK) return rc;
+  if (hipMemcpyAsync(out_resp, d_resp, N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_gprio, d_gprio, N * n * 4, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_sched, d_sched, N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
     return GCAPS_EDEVICE;

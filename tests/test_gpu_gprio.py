@@ -1,0 +1,150 @@
+"""GPU-segment priority assignment (Sec. 4.3 / 5.4) on the GPU against the CPU oracle, bit for
+bit: every assigned level (int32), every response time (int64, sentinels included), every
+verdict, through the C ABI."""
+import numpy as np
+import pytest
+
+from test_gpu_parity import few_gpu_tasks_workload, gpu, relaxed_workload  # noqa: F401 (fixture)
+
+pytestmark = pytest.mark.gpu
+
+GCAPS, BUSY, SUSPEND = 1, 0, 1
+
+
+def compare(oracle, B, ctx, batch, skip=None, waits=(BUSY, SUSPEND)):
+    found = 0
+    for wait in waits:
+        want_g, want_r, want_s, _ = oracle.gprio_assign_batch(batch, wait, skip=skip, threads=16)
+        got_g, got_r, got_s = B.gcaps_gprio_assign_batch(ctx, batch, wait, skip)
+        bad = np.argwhere(got_g != want_g)
+        assert bad.size == 0, (wait, bad[:5], got_g[bad[0][0]], want_g[bad[0][0]])
+        bad = np.argwhere(got_r != want_r)
+        assert bad.size == 0, (wait, bad[:5], got_r[bad[0][0]], want_r[bad[0][0]])
+        assert (got_s == want_s).all()
+        found += int(want_s.sum())
+    return found
+
+
+@pytest.mark.parametrize("k,N", [(1, None), (2, None), (3, 20_000), (4, 2_000), (5, 21_600)])
+def test_named_workloads(oracle, gpu, k, N):
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    print(f"workload {k} N={N}", flush=True)
+    compare(oracle, B, ctx, taskgen.config(k, N))
+
+
+def test_only_the_tasksets_that_fail_with_equal_priorities(oracle, gpu):
+    """The procedure of Sec. 6.1: separate priorities are searched for the tasksets that fail the
+    test with GPU priority = CPU priority; some of them are rescued."""
+    B, ctx, _ = gpu
+    batch = relaxed_workload(6_001, seed=4)
+    for wait in (BUSY, SUSPEND):
+        _, sched = B.gcaps_rta_batch(ctx, batch, GCAPS, wait)
+        skip = sched[0]
+        assert 0.05 < skip.mean() < 0.95
+        want_g, want_r, want_s, _ = oracle.gprio_assign_batch(batch, wait, skip=skip, threads=16)
+        got_g, got_r, got_s = B.gcaps_gprio_assign_batch(ctx, batch, wait, skip)
+        assert (got_g == want_g).all() and (got_r == want_r).all() and (got_s == want_s).all()
+        rescued = int((got_s.astype(bool) & ~skip.astype(bool)).sum())
+        assert rescued > 0
+        # an assignment that was found passes the analysis for given priorities, with the same bounds
+        for s in np.flatnonzero(got_s.astype(bool) & ~skip.astype(bool))[:40]:
+            r, ok, _ = oracle.gprio_rta_taskset(batch["cpu_us"][s], batch["period_us"][s], batch["deadline_us"][s],
+                                                batch["prio"][s], batch["core"][s], batch["n_gseg"][s],
+                                                batch["gm_us"][s], batch["ge_us"][s], got_g[s],
+                                                eps_us=batch["eps_us"][s], wait_mode=wait)
+            assert ok == 1 and (r == got_r[s]).all()
+
+
+def test_mostly_schedulable_tasksets(oracle, gpu):
+    B, ctx, _ = gpu
+    for batch in (relaxed_workload(5_003, seed=2), few_gpu_tasks_workload(5_003, seed=2)):
+        found = compare(oracle, B, ctx, batch)
+        assert 0.1 * 2 * 5_003 < found < 0.99 * 2 * 5_003
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 0), (1, 1, 1), (2, 1, 2), (3, 7, 1), (8, 4, 5), (4, 8, 2), (5, 13, 2),
+                                   (2, 3, 11), (2, 17, 4), (16, 2, 3)])
+def test_shapes_and_ragged_batches(oracle, gpu, shape):
+    B, ctx, _ = gpu
+    cores, per_core, S = shape
+    for N in (1, 15, 16, 17, 257):
+        compare(oracle, B, ctx, relaxed_workload(N, seed=N, n_cores=cores, per_core=per_core, S=S))
+
+
+def test_priority_ties_cpu_only_tasks_and_constrained_deadlines(oracle, gpu):
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(5)
+    batch = few_gpu_tasks_workload(3_000, seed=9)
+    batch["prio"] = rng.integers(-3, 4, batch["prio"].shape).astype(np.int32)
+    batch["n_gseg"] = np.where(rng.random(batch["n_gseg"].shape) < 0.4, 0, batch["n_gseg"]).astype(np.uint8)
+    batch["deadline_us"] = (batch["period_us"] * rng.uniform(0.6, 1.0, batch["period_us"].shape)).astype(np.uint32)
+    batch["core"] = rng.integers(0, 5, batch["core"].shape).astype(np.uint8)
+    found = compare(oracle, B, ctx, batch)
+    assert found > 300
+
+
+def test_values_beyond_24_bits(oracle, gpu):
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(6)
+    batch = relaxed_workload(1_500, seed=3, n_cores=2, per_core=4, S=2)
+    scale = rng.choice([1, 1, 300, 4000], size=(1500, 1)).astype(np.uint64)
+    for key in ("cpu_us", "period_us", "deadline_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale, 2**32 - 1).astype(np.uint32)
+    for key in ("gm_us", "ge_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale[:, :, None], 2**32 - 1).astype(np.uint32)
+    batch["eps_us"] = rng.choice([0, 200, 70_000, 2**31], size=1500).astype(np.uint32)
+    batch["prio"] = (batch["prio"].astype(np.int64) * rng.choice([1, 2**26], size=(1500, 1))).astype(np.int32)
+    found = compare(oracle, B, ctx, batch)
+    assert found > 100
+    big = 2**32 - 1
+    one = dict(theta_us=[big], eps_us=[big], slice_us=[1], cpu_us=[[big, 5]], period_us=[[big, big]],
+               deadline_us=[[big, big]], prio=[[2, 1]], core=[[0, 0]], n_gseg=[[3, 3]],
+               gm_us=[[[big] * 3] * 2], ge_us=[[[big] * 3] * 2])
+    compare(oracle, B, ctx, {k: np.array(v) for k, v in one.items()})
+    one.update(eps_us=[0], cpu_us=[[5, 5]], gm_us=[[[1] * 3] * 2], ge_us=[[[2**30] * 3, [7] * 3]], core=[[0, 1]])
+    assert compare(oracle, B, ctx, {k: np.array(v) for k, v in one.items()}) == 2
+
+
+def test_invalid_taskset_is_reported(gpu):
+    B, ctx, _ = gpu
+    batch = relaxed_workload(300, seed=1)
+    for key, value in (("period_us", 0), ("deadline_us", 0), ("n_gseg", 200)):
+        bad = {k: v.copy() for k, v in batch.items()}
+        bad[key][137, 2] = value
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_gprio_assign_batch(ctx, bad, BUSY)
+        assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 137
+    bad = {k: v.copy() for k, v in batch.items()}
+    bad["deadline_us"][5, 0] = bad["period_us"][5, 0] + 1
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_gprio_assign_batch(ctx, bad, SUSPEND)
+    assert e.value.first_bad == 5
+    # a skipped taskset is not looked at
+    skip = np.zeros(300, np.uint8)
+    skip[5] = 1
+    B.gcaps_gprio_assign_batch(ctx, bad, SUSPEND, skip)
+
+
+def test_device_entry_point_and_chunked_calls(oracle, gpu, monkeypatch):
+    import torch
+    B, ctx, stream = gpu
+    batch = relaxed_workload(3_001, seed=12)
+    d = B.to_device(batch)
+    N, n = batch["cpu_us"].shape
+    skip = (np.arange(N) % 5 == 0).astype(np.uint8)
+    want_g, want_r, want_s, _ = oracle.gprio_assign_batch(batch, SUSPEND, skip=skip, threads=16)
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "640")
+    ctx2 = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        for c in (ctx, ctx2):
+            g = torch.full((N, n), -7, dtype=torch.int32, device="cuda:0")
+            r = torch.full((N, n), -7, dtype=torch.int64, device="cuda:0")
+            s = torch.full((N,), 9, dtype=torch.uint8, device="cuda:0")
+            torch.cuda.synchronize()
+            B.gcaps_gprio_assign_batch_device(c, d, SUSPEND, torch.from_numpy(skip).to("cuda:0"), g, r, s)
+            B.gcaps_status(c)
+            assert (g.cpu().numpy() == want_g).all() and (r.cpu().numpy() == want_r).all()
+            assert (s.cpu().numpy() == want_s).all()
+    finally:
+        B.gcaps_destroy(ctx2)
