@@ -65,6 +65,11 @@ def main():
                     help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
                          "HBM byte counters collected over this command)")
     ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
+    ap.add_argument("--row", choices=["rta", "gprio"], default="rta",
+                    help="rta (default, the headline): both response-time analyses; gprio: the GPU-segment "
+                         "priority assignment (Sec. 4.3 / 5.4) for the tasksets that fail the GCAPS test with "
+                         "GPU priority = CPU priority, as in the procedure of Sec. 6.1")
+    ap.add_argument("--search-all", action="store_true", help="--row gprio: search every taskset, skip none")
     args = ap.parse_args()
     if args.print_csrc_hash:
         print(csrc_sha256())
@@ -90,6 +95,8 @@ def main():
         cores, per_core, S = taskgen.CONFIG_SHAPES[args.workload]
         batch = taskgen.config(args.workload, N)
     n = cores * per_core
+    if args.row == "gprio":
+        return bench_gprio(args, batch, N, cores, per_core, S)
     policy = B.GCAPS_POLICY_BOTH
     P = 2
 
@@ -190,6 +197,99 @@ def main():
                            tasksets=N, n_tasks=n, max_gseg=S, policy="gcaps+rr", wait_mode=head,
                            binning=args.binning),
                modes=modes, roofline=roofline, int32_valu=alu, cpu_baseline=cpu)
+    B.gcaps_destroy(ctx)
+    print(json.dumps(out))
+
+
+def bench_gprio(args, batch, N, cores, per_core, S):
+    """One step = the GPU-segment priority search over one device-resident batch; tasksets that pass
+    the GCAPS test with equal priorities are skipped (their flags are computed before the timed
+    region by the response-time analysis, which is what the procedure of Sec. 6.1 has at that point)."""
+    import numpy as np
+    import torch
+    from paper_2406_05221_amd import binding as B
+
+    n = cores * per_core
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    d = B.to_device(batch)
+    d_flags = torch.empty((1, N), dtype=torch.uint8, device="cuda:0")
+    d_r1 = torch.empty((1, N, n), dtype=torch.int64, device="cuda:0")
+    d_gprio = torch.empty((N, n), dtype=torch.int32, device="cuda:0")
+    d_resp = torch.empty((N, n), dtype=torch.int64, device="cuda:0")
+    d_sched = torch.empty((N,), dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    modes = {}
+    for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
+        B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_GCAPS, wait, d_r1, d_flags)
+        B.gcaps_status(ctx)
+        d_skip = None if args.search_all else d_flags[0].clone()
+        for _ in range(args.warmup):
+            B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            starts[k].record(stream)
+            B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio, d_resp, d_sched)
+            stops[k].record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        B.gcaps_status(ctx)
+        dev_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+        searched = N if d_skip is None else int(N - d_skip.sum().item())
+        found = int(d_sched.sum().item()) - (N - searched)
+        modes[name] = dict(wall_ms_per_step=(t1 - t0) * 1e3 / args.steps, device_ms_per_step=float(np.mean(dev_ms)),
+                           device_ms_median=float(np.median(dev_ms)), tasksets_per_s=N * args.steps / (t1 - t0),
+                           searched=searched, searched_per_s=searched * args.steps / (t1 - t0),
+                           assignments_found=found, tasksets_via_64bit_kernel=B.gcaps_last_wide_count(ctx),
+                           skip=None if d_skip is None else d_skip.cpu().numpy())
+    head = min(modes, key=lambda m: modes[m]["tasksets_per_s"])
+    head_wait = B.GCAPS_WAIT_BUSY if head == "busy" else B.GCAPS_WAIT_SUSPEND
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        sample = min(N, 200_000)
+        sub = {k: v[:sample] for k, v in batch.items()}
+        skip = modes[head]["skip"]
+        skip = None if skip is None else skip[:sample]
+        t0 = time.perf_counter()
+        want_g, want_r, want_s, _ = oracle.gprio_assign_batch(sub, head_wait, skip=skip, threads=threads)
+        t_all = time.perf_counter() - t0
+        B.gcaps_gprio_assign_batch_device(ctx, d, head_wait,
+                                          None if args.search_all else torch.from_numpy(modes[head]["skip"]).cuda(),
+                                          d_gprio, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        same = bool((d_gprio[:sample].cpu().numpy() == want_g).all() and (d_resp[:sample].cpu().numpy() == want_r).all()
+                    and (d_sched[:sample].cpu().numpy() == want_s).all())
+        cpu = dict(value=sample / t_all, unit="tasksets/s", cores=threads, kind="oracle",
+                   sample=f"first {sample} tasksets of the workload (same skip flags), {head} mode, "
+                          f"{threads} std::thread workers over tasksets",
+                   gpu_matches_oracle_on_sample=same)
+    for mm in modes.values():
+        mm.pop("skip")
+    m = modes[head]
+    per_searched = 4 + 1 + n * (4 * 4 + 2) + n * S * 8   # eps, skip flag; C, T, D, prio, core, eta; Gm, Ge
+    per_output = n * (4 + 8) + 1                         # level, bound; verdict
+    alg_bytes = m["searched"] * per_searched + (N - m["searched"]) * 1 + N * per_output
+    achieved = alg_bytes / (m["device_ms_per_step"] * 1e-3) / 1e9
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                    traffic=None, kernel="gcaps_gprio_assign_batch_device (all launches of one step)",
+                    algorithmic_bytes_per_step=alg_bytes)
+    out = dict(metric="tasksets through the GPU-segment priority search/sec, 1 MI355X", value=m["tasksets_per_s"],
+               unit="tasksets/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=m["wall_ms_per_step"],
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="u32", data="synthetic",
+               config=dict(workload=f"workload {args.workload}: {N} tasksets, {cores} cores x {per_core} tasks/core, "
+                                    f"up to {S} GPU segments/task; priority search for the tasksets that fail the "
+                                    f"GCAPS test with equal priorities ({m['searched']} of {N}); headline = slower "
+                                    f"waiting mode ({head})" if not args.search_all else
+                                    f"workload {args.workload}: {N} tasksets, priority search for every taskset; "
+                                    f"headline = slower waiting mode ({head})",
+                           tasksets=N, n_tasks=n, max_gseg=S, wait_mode=head, row="gprio"),
+               modes=modes, roofline=roofline, cpu_baseline=cpu)
     B.gcaps_destroy(ctx)
     print(json.dumps(out))
 

@@ -19,6 +19,7 @@
 #include "rta_deep.hip.inc"
 #include "rta_bin.hip.inc"
 #include "gprio_wide.hip.inc"
+#include "gprio_fast.hip.inc"
 
 namespace {
 
@@ -362,15 +363,39 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
   hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr,
                      first_chunk ? 1 : 0);
   if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
-  const u32 N = b->n_tasksets;
-  ctx->wide_only = true;
-  const u32 slots = wide_slots(ctx, N);
+  const u32 N = b->n_tasksets, n = b->n_tasks;
+  u32 *status = (u32 *)ctx->status.ptr;
+  /* the quad-lane kernel takes shapes up to 32 tasks; what it cannot represent in 24 bits it lists */
+  ctx->wide_only = n > 32 || gprio::gprio_lds_bytes(n) > (size_t)ctx->lds_limit;
+  const u32 *d_list = nullptr, *d_count = nullptr;
+  u32 items = N;
+  if (!ctx->wide_only) {
+    int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
+    if (rc != GCAPS_OK) return rc;
+    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+    const dim3 grid((N + 15u) / 16u), block(64);
+    const size_t lds = gprio::gprio_lds_bytes(n);
+    u32 *wl = (u32 *)ctx->wide_list.ptr;
+#define GCAPS_GPRIO_LAUNCH(BUSY, NS)                                                                              \
+  hipLaunchKernelGGL((gprio::gprio_fast_kernel<BUSY, NS>), grid, block, lds, ctx->stream, *b, d_skip, (int *)d_gprio, \
+                     (long long *)d_resp, d_sched, status, wl, ctx->ts_offset)
+    if (n <= 20) {
+      if (busy) GCAPS_GPRIO_LAUNCH(true, 5); else GCAPS_GPRIO_LAUNCH(false, 5);
+    } else {
+      if (busy) GCAPS_GPRIO_LAUNCH(true, 8); else GCAPS_GPRIO_LAUNCH(false, 8);
+    }
+#undef GCAPS_GPRIO_LAUNCH
+    if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+    d_list = wl;
+    d_count = status + fast::ST_WIDE_COUNT;
+    items = N < 65536u ? N : 65536u;
+  }
+  const u32 slots = wide_slots(ctx, items);
   wide::Scratch ws;
-  int rc = wide_columns(ctx, b->n_tasks, slots, &ws);
+  int rc = wide_columns(ctx, n, slots, &ws);
   if (rc != GCAPS_OK) return rc;
   hipLaunchKernelGGL(gprio::gprio_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, wait_mode, d_skip,
-                     (int *)d_gprio, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, (const u32 *)nullptr,
-                     (const u32 *)nullptr, ctx->ts_offset);
+                     (int *)d_gprio, (long long *)d_resp, d_sched, status, ws, d_list, d_count, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 

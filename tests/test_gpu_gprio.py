@@ -31,6 +31,9 @@ def test_named_workloads(oracle, gpu, k, N):
     B, ctx, _ = gpu
     print(f"workload {k} N={N}", flush=True)
     compare(oracle, B, ctx, taskgen.config(k, N))
+    # shapes up to 32 tasks with these magnitudes stay in the quad-lane kernel; workload 4 (80 tasks) does not
+    wide = B.gcaps_last_wide_count(ctx)
+    assert wide == (0 if k != 4 else 2_000)
 
 
 def test_only_the_tasksets_that_fail_with_equal_priorities(oracle, gpu):
@@ -97,6 +100,7 @@ def test_values_beyond_24_bits(oracle, gpu):
     batch["prio"] = (batch["prio"].astype(np.int64) * rng.choice([1, 2**26], size=(1500, 1))).astype(np.int32)
     found = compare(oracle, B, ctx, batch)
     assert found > 100
+    assert 100 < B.gcaps_last_wide_count(ctx) < 1500  # both kernels took part
     big = 2**32 - 1
     one = dict(theta_us=[big], eps_us=[big], slice_us=[1], cpu_us=[[big, 5]], period_us=[[big, big]],
                deadline_us=[[big, big]], prio=[[2, 1]], core=[[0, 0]], n_gseg=[[3, 3]],
