@@ -157,10 +157,10 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
     }
     status[1] = 0; /* length of the list for the 64-bit kernel */
     status[2] = 0; /* length of the ordered list for the second fast launch (binning only) */
-    status[4] = 0; /* next tile of the second fast launch */
   }
   status[fast::ST_DEEP_COUNTS + threadIdx.x] = 0; /* per-region lengths of the list for the second fast launch */
   for (u32 k = threadIdx.x; k < fast::kOrderBuckets; k += blockDim.x) status[fast::ST_ORDER_HIST + k] = 0;
+  status[fast::ST_CLAIM + threadIdx.x] = 0; /* tiles handed out by the persistent launch (kClaimCounters = 64 words) */
 }
 
 /* the list between the two fast launches: regions filled by the first launch, or (binning) the
@@ -371,14 +371,35 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
   u32 items = N;
   if (!ctx->wide_only) {
     int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
+    /* tiles of the first launch go to the list regions round-robin: a region never overflows */
+    const u32 producer_tiles = (N + 63u) / 64u;
+    ctx->region_cap = ((producer_tiles + fast::kListRegions - 1) / fast::kListRegions) * 64u;
+    if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32));
     if (rc != GCAPS_OK) return rc;
-    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
-    const dim3 grid((N + 15u) / 16u), block(64);
-    const size_t lds = gprio::gprio_lds_bytes(n);
+    const fast::ListSpec dl{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions,
+                            ctx->region_cap, nullptr, nullptr, nullptr};
     u32 *wl = (u32 *)ctx->wide_list.ptr;
-#define GCAPS_GPRIO_LAUNCH(BUSY, NS)                                                                              \
-  hipLaunchKernelGGL((gprio::gprio_fast_kernel<BUSY, NS>), grid, block, lds, ctx->stream, *b, d_skip, (int *)d_gprio, \
-                     (long long *)d_resp, d_sched, status, wl, ctx->ts_offset)
+    /* first launch: every taskset; settles what needs no search and lists the rest */
+    hipLaunchKernelGGL(gprio::gprio_screen_kernel, dim3(producer_tiles), dim3(64), 0, ctx->stream, *b, d_skip,
+                       (int *)d_gprio, (long long *)d_resp, d_sched, status, wl, dl, ctx->ts_offset);
+    if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+    /* second launch: the search, persistent workgroups over the list */
+    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+    const size_t lds = gprio::gprio_lds_bytes(n);
+    const void *fn = n <= 20 ? (busy ? (const void *)gprio::gprio_fast_kernel<true, 5> : (const void *)gprio::gprio_fast_kernel<false, 5>)
+                             : (busy ? (const void *)gprio::gprio_fast_kernel<true, 8> : (const void *)gprio::gprio_fast_kernel<false, 8>);
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
+      (void)hipGetLastError();
+      per_cu = 1;
+    }
+    u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
+    const u32 max_tiles = (N + 15u) / 16u + fast::kListRegions;
+    if (blocks > max_tiles) blocks = max_tiles;
+    const dim3 grid(blocks), block(64);
+#define GCAPS_GPRIO_LAUNCH(BUSY, NS)                                                                          \
+  hipLaunchKernelGGL((gprio::gprio_fast_kernel<BUSY, NS>), grid, block, lds, ctx->stream, *b, (int *)d_gprio, \
+                     (long long *)d_resp, d_sched, status, dl)
     if (n <= 20) {
       if (busy) GCAPS_GPRIO_LAUNCH(true, 5); else GCAPS_GPRIO_LAUNCH(false, 5);
     } else {
