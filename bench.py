@@ -27,8 +27,8 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="1c57df6e108ab82c64485387a87c40a22ff8ea2a71c58f44066da664751b8999",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943661990, write_bytes=333286451)
+MEASURED_TRAFFIC = dict(csrc_sha256="6b3011f22aa037cb9cfe9fffefbdb5c17690e67b096ede9d9169c6e1c17f1425",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943846195, write_bytes=333291315)
 
 
 def csrc_sha256():
