@@ -152,3 +152,44 @@ def test_device_entry_point_and_chunked_calls(oracle, gpu, monkeypatch):
             assert (s.cpu().numpy() == want_s).all()
     finally:
         B.gcaps_destroy(ctx2)
+
+
+# ---- full sizes, in the launch configuration the benchmark times (device entry point, skip flags from the
+# ---- response-time analysis with equal priorities) ----
+@pytest.mark.parametrize("k,first,N", [(3, 0, 1_000_000), (4, 0, 100_000), (5, 0, 1_000_000), (5, 7_000_000, 1_000_000),
+                                       (0, 0, 300_000)])
+def test_full_size_workloads_device_entry(oracle, gpu, k, first, N):
+    import torch
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    print(f"workload {k} tasksets [{first}, {first + N})", flush=True)
+    batch = relaxed_workload(N, seed=21) if k == 0 else taskgen.config(k, N, first_index=first)
+    d = B.to_device(batch)
+    n = batch["cpu_us"].shape[1]
+    d_r1 = torch.empty((1, N, n), dtype=torch.int64, device="cuda:0")
+    d_flags = torch.empty((1, N), dtype=torch.uint8, device="cuda:0")
+    d_gprio = torch.empty((N, n), dtype=torch.int32, device="cuda:0")
+    d_resp = torch.empty((N, n), dtype=torch.int64, device="cuda:0")
+    d_sched = torch.empty((N,), dtype=torch.uint8, device="cuda:0")
+    for wait in (BUSY, SUSPEND):
+        B.gcaps_rta_batch_device(ctx, d, GCAPS, wait, d_r1, d_flags)
+        B.gcaps_status(ctx)
+        d_skip = d_flags[0].clone()
+        d_gprio.fill_(-7)
+        d_resp.fill_(-7)
+        d_sched.fill_(9)
+        torch.cuda.synchronize()
+        B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        skip = d_skip.cpu().numpy()
+        want_g, want_r, want_s, _ = oracle.gprio_assign_batch(batch, wait, skip=skip, threads=16)
+        got_g, got_r, got_s = d_gprio.cpu().numpy(), d_resp.cpu().numpy(), d_sched.cpu().numpy()
+        assert np.array_equal(got_g, want_g), np.argwhere(got_g != want_g)[:5]
+        assert np.array_equal(got_r, want_r), np.argwhere(got_r != want_r)[:5]
+        assert np.array_equal(got_s, want_s)
+        # properties that hold at any size: a found assignment is a permutation of the levels 1..n and
+        # every bound is within its deadline; everything else is all-zero / not analysed
+        found = (got_s == 1) & (skip == 0)
+        assert (np.sort(got_g[found], axis=1) == np.arange(1, n + 1)).all()
+        assert (got_r[found] <= batch["deadline_us"][found]).all() and (got_r[found] > 0).all()
+        assert (got_g[~found] == 0).all() and (got_r[~found] == -2).all()
