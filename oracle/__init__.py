@@ -20,6 +20,7 @@ POLICY_BOTH = 3
 WAIT_BUSY = 0
 WAIT_SUSPEND = 1
 OPT_LITERAL_LEMMA10 = 1
+OPT_CONTINUE_AFTER_MISS = 2
 RESP_MISS = -1
 RESP_NOT_ANALYSED = -2
 OK = 0

@@ -337,7 +337,7 @@ extern "C" int oracle_rta_taskset(uint32_t n_tasks, uint32_t max_gseg, uint32_t 
   bool missed = false;
   for (uint32_t k = 0; k < n_tasks; ++k) {
     uint32_t i = order[k];
-    if (missed) {
+    if (missed && !(options & ORACLE_OPT_CONTINUE_AFTER_MISS)) {
       resp[i] = ORACLE_RESP_NOT_ANALYSED;
       continue;
     }
@@ -360,6 +360,9 @@ extern "C" int oracle_rta_taskset(uint32_t n_tasks, uint32_t max_gseg, uint32_t 
     } else {
       missed = true;
       resp[i] = ORACLE_RESP_MISS;
+      /* the response time of tau_k is unknown from here on: the jitters of the tasks below take
+       * D_k in its place (proof of Lemma 10) */
+      tau[k].R = tau[k].D;
     }
   }
   *sched = missed ? 0 : 1;

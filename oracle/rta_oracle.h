@@ -44,6 +44,12 @@ extern "C" {
 
 /* option bits */
 #define ORACLE_OPT_LITERAL_LEMMA10 1u /* keep the eta^g_i > 0 guard on the same-core sum of Lemma 10 */
+/* Go on after a task whose bound exceeds its deadline: its response time is unknown, so the
+ * jitters J^c_h, J^g_h of the tasks below it take D_h in place of R_h (proof of Lemma 10).  Every
+ * task is analysed: resp[i] = R_i or ORACLE_RESP_MISS, never ORACLE_RESP_NOT_ANALYSED; the verdict
+ * is unchanged.  Pins: equal to the default up to the first miss, a hand-worked four-task example,
+ * bounds never above those with D_h in every jitter (Sec. 5.4 with GPU = CPU priorities). */
+#define ORACLE_OPT_CONTINUE_AFTER_MISS 2u
 
 /* response-time sentinels */
 #define ORACLE_RESP_MISS (-1)         /* first task (in priority order) whose bound exceeds D_i */

@@ -8,6 +8,7 @@ import types
 
 import pytest
 
+import test_oracle_continue as continue_tests
 import test_oracle_des as des_tests
 import test_oracle_gprio as gprio_tests
 import test_oracle_pins as pin_tests
@@ -76,6 +77,8 @@ MUTANTS = {
     "search_levels_from_the_top": ("level_of[k] = (int32_t)level;", "level_of[k] = (int32_t)(n_tasks + 1 - level);"),
     "search_puts_assigned_tasks_above": ("      std::vector<char> higher_g(unassigned);\n      higher_g[k] = 0;",
                                          "      std::vector<char> higher_g(n_tasks, 1);"),
+    "continue_after_miss_takes_the_period": ("      tau[k].R = tau[k].D;\n", "      tau[k].R = tau[k].T;\n"),
+    "continue_after_miss_takes_zero": ("      tau[k].R = tau[k].D;\n", "      tau[k].R = 0;\n"),
     "stops_one_iteration_early": ("      } else if (next == R) {\n        break;",
                                   "      } else if (next == R || true) {\n        break;"),
 }
@@ -97,6 +100,9 @@ PINS = [
     des_tests.test_directed_carry_in_other_core,
     des_tests.test_directed_self_suspension_same_core,
     lambda o: [des_tests.test_simulated_response_never_exceeds_bound(o, p, w) for p, w in pin_tests.VARIANTS],
+    continue_tests.test_hand_worked_example,
+    continue_tests.test_every_task_missing_equals_deadline_jitters,
+    lambda o: [continue_tests.test_relations_with_the_default_and_with_deadline_jitters(o, 1, w) for w in (0, 1)],
     gprio_tests.test_table2_printed_verdicts,
     gprio_tests.test_table2_hand_worked_values,
     gprio_tests.test_runlist_update_cost_hand_worked,
