@@ -197,6 +197,17 @@ int gcaps_gprio_assign_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, in
  */
 int gcaps_set_binning(gcaps_ctx *ctx, int enable);
 
+/*
+ * Continue-after-miss (off by default) for gcaps_rta_batch / gcaps_rta_batch_device: the analysis
+ * of a taskset goes on below a task whose bound exceeds its deadline.  The response time of that
+ * task is unknown, so the jitters J^c_h, J^g_h of the tasks below it take D_h in place of R_h
+ * (proof of Lemma 10; a jitter is not taken below zero).  Every task is analysed: out_resp holds
+ * R_i or GCAPS_RESP_MISS and never GCAPS_RESP_NOT_ANALYSED; out_sched is unchanged.  Nothing can be
+ * settled from the highest-priority tasks alone in this mode: expect several times the run time.
+ * enable: 0 or 1.
+ */
+int gcaps_set_continue_after_miss(gcaps_ctx *ctx, int enable);
+
 /* Static description of an error code. */
 const char *gcaps_strerror(int code);
 

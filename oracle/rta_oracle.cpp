@@ -122,9 +122,10 @@ struct Analysis {
   /* starred demands of Sec. 5.3 */
   i64 Ge_star(const Task &t) const { return add(t.Ge, mul(2 * p.eps, t.eta)); }
   i64 Gm_star(const Task &t) const { return add(t.Gm, mul(2 * p.eps, t.eta)); }
-  /* jitters of Lemma 7 and Lemma 10 */
-  i64 Jc(const Task &h) const { return h.R - (h.C + h.Gm); }
-  i64 Jg(const Task &h) const { return h.R - h.Ge; }
+  /* jitters of Lemma 7 and Lemma 10.  R_h >= C_h + G_h for a task that met its deadline; where
+   * D_h stands in for an unknown R_h (continue-after-miss) a jitter is not taken below zero */
+  i64 Jc(const Task &h) const { return std::max<i64>(0, h.R - (h.C + h.Gm)); }
+  i64 Jg(const Task &h) const { return std::max<i64>(0, h.R - h.Ge); }
 
   i64 term(i64 window, i64 period, i64 cost) {
     ++terms;
@@ -245,8 +246,10 @@ struct GprioAnalysis {
   i64 updates(size_t h) const { return mul(2 * p.eps, tau[h].eta); } /* 2*eps per GPU segment, Sec. 5.3 */
   i64 ge_star(size_t h) const { return add(tau[h].Ge, updates(h)); }
   i64 gm_star(size_t h) const { return add(tau[h].Gm, updates(h)); }
-  i64 jitter_c(size_t h) const { return tau[h].D - (tau[h].C + tau[h].Gm); } /* Lemma 7's J^c_h, D_h for R_h */
-  i64 jitter_g(size_t h) const { return tau[h].D - tau[h].Ge; }             /* Lemma 10's J^g_h, D_h for R_h */
+  /* Lemma 7's J^c_h and Lemma 10's J^g_h with D_h for R_h; not below zero (only a task whose own
+   * demand exceeds its deadline gets there, and the search settles such tasksets beforehand) */
+  i64 jitter_c(size_t h) const { return std::max<i64>(0, tau[h].D - (tau[h].C + tau[h].Gm)); }
+  i64 jitter_g(size_t h) const { return std::max<i64>(0, tau[h].D - tau[h].Ge); }
 
   i64 arrivals_times(i64 window, size_t h, i64 cost) {
     ++terms;

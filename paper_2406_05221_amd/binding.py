@@ -25,7 +25,7 @@ GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
-           "gcaps_gprio_assign_batch_device"]
+           "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -55,6 +55,8 @@ _lib.gcaps_gprio_assign_batch.restype = _int
 _lib.gcaps_gprio_assign_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p, ctypes.POINTER(_u32)]
 _lib.gcaps_gprio_assign_batch_device.restype = _int
 _lib.gcaps_gprio_assign_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p]
+_lib.gcaps_set_continue_after_miss.restype = _int
+_lib.gcaps_set_continue_after_miss.argtypes = [_p, _int]
 _lib.gcaps_strerror.restype = ctypes.c_char_p
 _lib.gcaps_strerror.argtypes = [_int]
 
@@ -98,6 +100,12 @@ def gcaps_destroy(ctx):
 
 def gcaps_set_binning(ctx, enable):
     rc = _lib.gcaps_set_binning(ctx, int(enable))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+
+
+def gcaps_set_continue_after_miss(ctx, enable):
+    rc = _lib.gcaps_set_continue_after_miss(ctx, int(enable))
     if rc != GCAPS_OK:
         raise GcapsError(rc)
 

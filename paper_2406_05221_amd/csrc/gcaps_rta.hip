@@ -61,6 +61,7 @@ struct gcaps_ctx {
   hipStream_t stream = nullptr;
   int n_cu = 0;
   int binning = 0;
+  int cont = 0;             /* continue-after-miss (gcaps_set_continue_after_miss) */
   u64 chunk_cap = 0;        /* GCAPS_CHUNK_TASKSETS: smaller chunks than the 32-bit limit needs (testing) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
   u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
@@ -141,7 +142,7 @@ int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   if (rc != GCAPS_OK) return rc;
   hipLaunchKernelGGL(wide::rta_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, policy,
                      wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count,
-                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset, ctx->cont != 0);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -238,10 +239,11 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
   u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
   const u32 max_tiles = (N + ts - 1) / ts + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
-  const fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0);
+  fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0 && !ctx->cont);
+  if (ctx->cont) dl = fast::ListSpec{nullptr, nullptr, 1u, N, nullptr, nullptr, nullptr}; /* every taskset */
   hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
                      (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl, kr,
-                     ctx->resp_stride, ctx->sched_stride);
+                     ctx->resp_stride, ctx->sched_stride, ctx->cont != 0, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -273,6 +275,8 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
   const int ts_screen = n <= fast::kMaxTasks ? tile_width(ctx, n, kr) : 0;
   ctx->wide_only = ts_screen == 0 || (kr < n && fast::deep_lds_bytes(n, ctx->deep_lanes) > (size_t)ctx->lds_limit);
+  if (ctx->cont) /* the full-depth launch alone */
+    ctx->wide_only = n > fast::kMaxTasks || fast::deep_lds_bytes(n, ctx->deep_lanes) > (size_t)ctx->lds_limit;
   if (ctx->wide_only) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
   int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
   /* tiles of the first launch go to the list regions round-robin: a region never overflows */
@@ -282,6 +286,15 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   if (rc == GCAPS_OK && ctx->binning)
     rc = ctx->deep_aux.reserve((size_t)ctx->region_cap * fast::kListRegions * 2 * sizeof(u32));
   if (rc != GCAPS_OK) return rc;
+
+  if (ctx->cont) {
+    /* continue-after-miss: nothing is settled early, the full-depth launch takes every taskset */
+    rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched, 0u);
+    if (rc != GCAPS_OK) return rc;
+    const u32 *count = (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT;
+    return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count,
+                       N < 65536u ? N : 65536u);
+  }
 
   /* first launch: every taskset, the kr highest-priority tasks only */
   const u32 tiles = (N + (u32)ts_screen - 1) / (u32)ts_screen;
@@ -568,6 +581,12 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
 extern "C" int gcaps_set_binning(gcaps_ctx *ctx, int enable) {
   if (!ctx || (enable != 0 && enable != 1)) return GCAPS_EINVAL;
   ctx->binning = enable;
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_set_continue_after_miss(gcaps_ctx *ctx, int enable) {
+  if (!ctx || (enable != 0 && enable != 1)) return GCAPS_EINVAL;
+  ctx->cont = enable;
   return GCAPS_OK;
 }
 

@@ -46,6 +46,7 @@ def test_argument_errors_need_no_device(binding):
     assert lib.gcaps_rta_batch_device(None, None, 3, 0, None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_status(None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_set_binning(None, 1) == binding.GCAPS_EINVAL
+    assert lib.gcaps_set_continue_after_miss(None, 1) == binding.GCAPS_EINVAL
     assert lib.gcaps_last_wide_count(None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_gprio_assign_batch(None, None, 0, None, None, None, None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_gprio_assign_batch_device(None, None, 0, None, None, None, None) == binding.GCAPS_EINVAL

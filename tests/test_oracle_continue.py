@@ -30,6 +30,21 @@ def test_hand_worked_example(oracle):
     assert list(resp) == [10, -1, 51, 31] and sched == 0
 
 
+def test_jitter_is_not_taken_below_zero(oracle):
+    """tau_a's own GPU time alone exceeds its deadline: D_a - G^e_a < 0, the jitter is 0.  GCAPS,
+    busy-waiting, eps = 0, other core: tau_b = 10 + ceil(R/100)*40: 10 -> 50 -> 50 (with a jitter of
+    30-40 = -10 the window would shrink; with |.| or D_a it would not change here, so the deadline
+    of tau_b is set to make one more arrival visible: R = 50+J crosses 100 only for J > 50)."""
+    a = dict(C=1, T=100, D=30, prio=2, core=0, gm=[0], ge=[40])
+    b = dict(C=4, T=500, D=500, prio=1, core=1, gm=[0], ge=[6])
+    resp, _, _ = oracle_bound(oracle, [a, b], GCAPS, BUSY, 0, 0, 1, options=oracle.OPT_CONTINUE_AFTER_MISS)
+    assert list(resp) == [-1, 50]
+    # ceil((R + J)/100) with J = -10 and R = 10 would be ceil(0/100) = 0 arrivals: 10, not 50
+    b2 = dict(b, C=0, ge=[10])
+    resp, _, _ = oracle_bound(oracle, [a, b2], GCAPS, BUSY, 0, 0, 1, options=oracle.OPT_CONTINUE_AFTER_MISS)
+    assert list(resp) == [-1, 50]
+
+
 def test_round_robin_busy_has_no_jitter_to_replace(oracle):
     """Lemmas 4 and 5 use no response time of another task: below a miss every bound is what it
     would be had the task above met its deadline.  tau_b misses (1 > its deadline is forced by D = 1)."""

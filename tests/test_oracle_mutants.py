@@ -19,10 +19,13 @@ SRC = os.path.join(ROOT, "oracle", "rta_oracle.cpp")
 MUTANTS = {
     "lemma10_same_core_sum_dropped": (
         "bool first_sum = tau[i].gpu() || !(options & ORACLE_OPT_LITERAL_LEMMA10);", "bool first_sum = false;"),
-    "jitter_Jg_dropped": ("i64 Jg(const Task &h) const { return h.R - h.Ge; }",
+    "jitter_Jg_dropped": ("i64 Jg(const Task &h) const { return std::max<i64>(0, h.R - h.Ge); }",
                           "i64 Jg(const Task &h) const { (void)h; return 0; }"),
-    "jitter_Jc_dropped": ("i64 Jc(const Task &h) const { return h.R - (h.C + h.Gm); }",
+    "jitter_Jc_dropped": ("i64 Jc(const Task &h) const { return std::max<i64>(0, h.R - (h.C + h.Gm)); }",
                           "i64 Jc(const Task &h) const { (void)h; return 0; }"),
+    "jitter_below_zero_when_own_demand_exceeds_the_deadline": (
+        "i64 Jg(const Task &h) const { return std::max<i64>(0, h.R - h.Ge); }",
+        "i64 Jg(const Task &h) const { return h.R - h.Ge; }"),
     "lemma4_tau_h_not_counted": ("    i64 nu = 1;", "    i64 nu = 0;"),
     "lemma8_blocking_dropped": ("b = add(b, mul(t.eta + 1, p.eps));", "b = add(b, 0);"),
     "lemma8_blocking_eta_only": ("b = add(b, mul(t.eta + 1, p.eps));", "b = add(b, mul(t.eta, p.eps));"),
@@ -46,16 +49,16 @@ MUTANTS = {
                                  "bool same_core(size_t h, size_t i) const { return tau[h].core != tau[i].core; }"),
     "priority_order_reversed": ("return prio[a] > prio[b]; });", "return prio[a] < prio[b]; });"),
     "G_i_without_Gm": ("t.G = t.Gm + t.Ge;", "t.G = t.Ge;"),
-    "gprio_jitter_Jg_dropped": ("i64 jitter_g(size_t h) const { return tau[h].D - tau[h].Ge; }",
+    "gprio_jitter_Jg_dropped": ("i64 jitter_g(size_t h) const { return std::max<i64>(0, tau[h].D - tau[h].Ge); }",
                                 "i64 jitter_g(size_t h) const { (void)h; return 0; }"),
-    "gprio_jitter_Jg_from_deadline_only": ("i64 jitter_g(size_t h) const { return tau[h].D - tau[h].Ge; }",
+    "gprio_jitter_Jg_from_deadline_only": ("i64 jitter_g(size_t h) const { return std::max<i64>(0, tau[h].D - tau[h].Ge); }",
                                            "i64 jitter_g(size_t h) const { return tau[h].D; }"),
     "gprio_jitter_Jc_from_deadline_only": (
-        "i64 jitter_c(size_t h) const { return tau[h].D - (tau[h].C + tau[h].Gm); }",
+        "i64 jitter_c(size_t h) const { return std::max<i64>(0, tau[h].D - (tau[h].C + tau[h].Gm)); }",
         "i64 jitter_c(size_t h) const { return tau[h].D; }"),
     "gprio_lemma11_dropped": ("      /* Lemma 10, second sum (eta^g_i > 0); Lemma 11 (eta^g_i = 0) */\n      for (size_t h = 0; h < n; ++h)\n        if (higher_g[h] &&",
                               "      for (size_t h = 0; h < n; ++h)\n        if (uses_gpu(i) && higher_g[h] &&"),
-    "gprio_jitter_Jc_dropped": ("i64 jitter_c(size_t h) const { return tau[h].D - (tau[h].C + tau[h].Gm); }",
+    "gprio_jitter_Jc_dropped": ("i64 jitter_c(size_t h) const { return std::max<i64>(0, tau[h].D - (tau[h].C + tau[h].Gm)); }",
                                 "i64 jitter_c(size_t h) const { (void)h; return 0; }"),
     "gprio_Ge_star_without_updates": ("i64 ge_star(size_t h) const { return add(tau[h].Ge, updates(h)); }",
                                       "i64 ge_star(size_t h) const { return tau[h].Ge; }"),
@@ -101,6 +104,7 @@ PINS = [
     des_tests.test_directed_self_suspension_same_core,
     lambda o: [des_tests.test_simulated_response_never_exceeds_bound(o, p, w) for p, w in pin_tests.VARIANTS],
     continue_tests.test_hand_worked_example,
+    continue_tests.test_jitter_is_not_taken_below_zero,
     continue_tests.test_every_task_missing_equals_deadline_jitters,
     lambda o: [continue_tests.test_relations_with_the_default_and_with_deadline_jitters(o, 1, w) for w in (0, 1)],
     gprio_tests.test_table2_printed_verdicts,
