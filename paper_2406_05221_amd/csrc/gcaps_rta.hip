@@ -223,7 +223,7 @@ int launch_fast(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
 }
 
 /* second launch: the listed tasksets in full, 64 / Q per wavefront; persistent workgroups */
-template <bool BUSY, int Q>
+template <bool BUSY, int Q, bool CONT>
 int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_resp, uint8_t *d_sched, u32 kr) {
   const u32 n = b->n_tasks, N = b->n_tasksets, ts = 64u / (u32)Q;
   const size_t lds = fast::deep_lds_bytes(n, Q);
@@ -231,7 +231,7 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
    * workgroup's first tile is its own index, so one that had to wait for a free slot would start
    * that tile only after the others have drained the queue. */
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fast::rta_deep_kernel<BUSY, Q>, 64, lds) != hipSuccess ||
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fast::rta_deep_kernel<BUSY, Q, CONT>, 64, lds) != hipSuccess ||
       per_cu < 1) {
     (void)hipGetLastError();
     per_cu = 1;
@@ -239,22 +239,29 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
   u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
   const u32 max_tiles = (N + ts - 1) / ts + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
-  fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0 && !ctx->cont);
-  if (ctx->cont) dl = fast::ListSpec{nullptr, nullptr, 1u, N, nullptr, nullptr, nullptr}; /* every taskset */
-  hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+  fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0 && !CONT);
+  if (CONT) dl = fast::ListSpec{nullptr, nullptr, 1u, N, nullptr, nullptr, nullptr}; /* every taskset */
+  hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q, CONT>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
                      (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl, kr,
-                     ctx->resp_stride, ctx->sched_stride, ctx->cont != 0, ctx->ts_offset);
+                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+template <bool CONT>
+int launch_deep_c(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                  uint8_t *d_sched, u32 kr) {
+  const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+  if (ctx->deep_lanes == 8)
+    return busy ? launch_deep_q<true, 8, CONT>(ctx, b, policy, d_resp, d_sched, kr)
+                : launch_deep_q<false, 8, CONT>(ctx, b, policy, d_resp, d_sched, kr);
+  return busy ? launch_deep_q<true, 4, CONT>(ctx, b, policy, d_resp, d_sched, kr)
+              : launch_deep_q<false, 4, CONT>(ctx, b, policy, d_resp, d_sched, kr);
 }
 
 int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr) {
-  const bool busy = wait_mode == GCAPS_WAIT_BUSY;
-  if (ctx->deep_lanes == 8)
-    return busy ? launch_deep_q<true, 8>(ctx, b, policy, d_resp, d_sched, kr)
-                : launch_deep_q<false, 8>(ctx, b, policy, d_resp, d_sched, kr);
-  return busy ? launch_deep_q<true, 4>(ctx, b, policy, d_resp, d_sched, kr)
-              : launch_deep_q<false, 4>(ctx, b, policy, d_resp, d_sched, kr);
+  return ctx->cont ? launch_deep_c<true>(ctx, b, policy, wait_mode, d_resp, d_sched, kr)
+                   : launch_deep_c<false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr);
 }
 
 /* widest tile (tasksets per wavefront) whose LDS rows fit, 0 if none */
@@ -540,9 +547,11 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_fast_kernel<64, 8>,  (const void *)fast::rta_fast_kernel<64, 16>,
         (const void *)fast::rta_fast_kernel<64, 24>, (const void *)fast::rta_fast_kernel<64, 32>,
         (const void *)fast::rta_fast_kernel<32, 0>,  (const void *)fast::rta_fast_kernel<16, 0>,
-        (const void *)fast::rta_screen_kernel<true>,   (const void *)fast::rta_screen_kernel<false>,       (const void *)fast::rta_deep_kernel<true, 4>,
-        (const void *)fast::rta_deep_kernel<false, 4>,        (const void *)fast::rta_deep_kernel<true, 8>,
-        (const void *)fast::rta_deep_kernel<false, 8>};
+        (const void *)fast::rta_screen_kernel<true>, (const void *)fast::rta_screen_kernel<false>,
+        (const void *)fast::rta_deep_kernel<true, 4, false>, (const void *)fast::rta_deep_kernel<false, 4, false>,
+        (const void *)fast::rta_deep_kernel<true, 8, false>, (const void *)fast::rta_deep_kernel<false, 8, false>,
+        (const void *)fast::rta_deep_kernel<true, 4, true>, (const void *)fast::rta_deep_kernel<false, 4, true>,
+        (const void *)fast::rta_deep_kernel<true, 8, true>, (const void *)fast::rta_deep_kernel<false, 8, true>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
