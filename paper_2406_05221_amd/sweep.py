@@ -1,0 +1,71 @@
+"""Schedulability sweeps in the manner of Sec. 6.1: the share of randomly generated tasksets that
+pass the response-time test, per analysis, while one generation parameter of Table 3 is varied.
+
+    python -m paper_2406_05221_amd.sweep --param util --values 0.2,0.3,0.4,0.5,0.6 --tasksets 1000
+
+Columns: the default round-robin TSG scheduling (Sec. 5.2) and GCAPS (Sec. 5.3), each with
+busy-waiting and self-suspension, and GCAPS with the GPU-segment priority assignment tried for the
+tasksets that fail with equal priorities (Sec. 4.3 / 5.4, the procedure of Sec. 6.1).  Everything
+is computed by the GPU library; this module only draws inputs, groups them by task count (a batch
+of the library has one task count) and averages verdicts."""
+import argparse
+
+import numpy as np
+
+from . import binding as B
+from . import taskgen
+
+COLUMNS = ["tsg_rr_busy", "tsg_rr_suspend", "gcaps_busy", "gcaps_suspend", "gcaps_busy+prio", "gcaps_suspend+prio"]
+
+
+def verdicts(ctx, groups):
+    """groups: {n: (indices, batch)} as returned by ``taskgen.table3``.  Returns a dict of uint8
+    arrays over the generated tasksets (generation order), one per column."""
+    total = sum(len(idx) for idx, _ in groups.values())
+    out = {c: np.zeros(total, np.uint8) for c in COLUMNS}
+    for idx, batch in groups.values():
+        for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
+            _, sched = B.gcaps_rta_batch(ctx, batch, B.GCAPS_POLICY_BOTH, wait)
+            out[f"gcaps_{name}"][idx] = sched[0]
+            out[f"tsg_rr_{name}"][idx] = sched[1]
+            # separate GPU-segment priorities only where the test with equal priorities failed
+            _, _, found = B.gcaps_gprio_assign_batch(ctx, batch, wait, skip=sched[0])
+            out[f"gcaps_{name}+prio"][idx] = found
+    return out
+
+
+def sweep(ctx, param, values, n_tasksets, seed=0):
+    """One row per value of `param` (a key of ``taskgen.TABLE3``; range parameters are set to the
+    single value): the share of schedulable tasksets per column."""
+    rows = []
+    for k, v in enumerate(values):
+        value = (v, v) if isinstance(taskgen.TABLE3[param], tuple) else v
+        groups = taskgen.table3(n_tasksets, seed=seed, stream=300 + k, **{param: value})
+        res = verdicts(ctx, groups)
+        rows.append((v, {c: float(res[c].mean()) for c in COLUMNS}))
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--param", default="util", choices=sorted(taskgen.TABLE3))
+    ap.add_argument("--values", default="0.2,0.3,0.4,0.5,0.6,0.7")
+    ap.add_argument("--tasksets", type=int, default=1000, help="tasksets per point (the paper uses 1,000)")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    cast = int if isinstance(taskgen.TABLE3[args.param], int) or args.param in ("tasks_per_cpu", "period", "eta") \
+        else float
+    values = [cast(x) for x in args.values.split(",")]
+    ctx = B.gcaps_create(0)
+    try:
+        rows = sweep(ctx, args.param, values, args.tasksets, args.seed)
+    finally:
+        B.gcaps_destroy(ctx)
+    print(f"| {args.param} | " + " | ".join(COLUMNS) + " |")
+    print("|---|" + "---|" * len(COLUMNS))
+    for v, r in rows:
+        print(f"| {v} | " + " | ".join(f"{100 * r[c]:.1f} %" for c in COLUMNS) + " |")
+
+
+if __name__ == "__main__":
+    main()

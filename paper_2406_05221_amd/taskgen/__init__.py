@@ -38,6 +38,9 @@ def _load():
         _lib.taskgen_generate.restype = ctypes.c_int
         _lib.taskgen_generate.argtypes = ([u64, u64, u64, u32, u32, u32, u32, dbl, dbl, p, u32, u32, dbl, dbl, p,
                                            u32, u32, u32, u32, p, u32, p, i32] + [p] * 11)
+        _lib.taskgen_table3.restype = ctypes.c_int
+        _lib.taskgen_table3.argtypes = ([u64, u64, u64, u32, u32, u32, u32, u32, dbl, dbl, dbl, dbl, u32, u32, u32, u32,
+                                         dbl, dbl, dbl, dbl, u32, u32, u32, i32] + [p] * 12)
     return _lib
 
 
@@ -120,3 +123,50 @@ def config(k, n_tasksets=None, *, first_index=0, seed=0, threads=None):
                         share=np.ascontiguousarray(cell[:, 1]), period=(1_000, 1_000_000),
                         overhead=cell[:, 2].astype(np.uint32), slice_us=cell[:, 3].astype(np.uint32), **common)
     raise ValueError(f"unknown workload {k}")
+
+
+# ---- the recipe of the paper's schedulability experiments (Sec. 6.1, Table 3) ---------------------
+TABLE3 = dict(n_cpus=4, tasks_per_cpu=(3, 6), gpu_ratio=(0.4, 0.6), util=(0.4, 0.6), period=(30_000, 500_000),
+              eta=(1, 3), g_over_c=(0.2, 2.0), gm_over_g=(0.1, 0.3), theta_us=200, eps_us=1000, slice_us=1024)
+
+
+def table3(n_tasksets, *, seed=0, stream=300, first_index=0, threads=None, **overrides):
+    """Tasksets drawn by the recipe of Sec. 6.1 with the ranges of Table 3 (any of them can be
+    overridden by keyword, e.g. ``util=(0.5, 0.5)`` for one point of a sweep): tasks per CPU drawn
+    per CPU, UUniFast per CPU, uniform periods, a share of GPU-using tasks, G/C and G^m/G ratios,
+    rate-monotonic priorities, worst-fit-decreasing re-allocation to the CPUs.
+
+    Tasksets differ in their number of tasks, a batch of the library does not: the result is a dict
+    {n: (indices, batch)} with one batch per task count n, `indices` saying which of the generated
+    tasksets (in generation order) the rows of the batch are."""
+    q = dict(TABLE3)
+    unknown = set(overrides) - set(q)
+    if unknown:
+        raise ValueError(f"unknown Table 3 parameters: {sorted(unknown)}")
+    q.update(overrides)
+    N = int(n_tasksets)
+    n_max, S = q["n_cpus"] * q["tasks_per_cpu"][1], q["eta"][1]
+    count = np.zeros(N, np.uint32)
+    out = dict(theta_us=np.empty(N, np.uint32), eps_us=np.empty(N, np.uint32), slice_us=np.empty(N, np.uint32),
+               cpu_us=np.empty((N, n_max), np.uint32), period_us=np.empty((N, n_max), np.uint32),
+               deadline_us=np.empty((N, n_max), np.uint32), prio=np.empty((N, n_max), np.int32),
+               core=np.empty((N, n_max), np.uint8), n_gseg=np.empty((N, n_max), np.uint8),
+               gm_us=np.empty((N, n_max, S), np.uint32), ge_us=np.empty((N, n_max, S), np.uint32))
+    if threads is None:
+        threads = min(16, os.cpu_count() or 1)
+    rc = _load().taskgen_table3(seed, stream, first_index, N, q["n_cpus"], q["tasks_per_cpu"][0], q["tasks_per_cpu"][1],
+                                S, float(q["gpu_ratio"][0]), float(q["gpu_ratio"][1]), float(q["util"][0]),
+                                float(q["util"][1]), q["period"][0], q["period"][1], q["eta"][0], q["eta"][1],
+                                float(q["g_over_c"][0]), float(q["g_over_c"][1]), float(q["gm_over_g"][0]),
+                                float(q["gm_over_g"][1]), q["theta_us"], q["eps_us"], q["slice_us"], threads,
+                                _ptr(count), *[_ptr(out[k]) for k in ("theta_us", "eps_us", "slice_us", "cpu_us",
+                                                                      "period_us", "deadline_us", "prio", "core",
+                                                                      "n_gseg", "gm_us", "ge_us")])
+    if rc != 0:
+        raise ValueError("taskgen: invalid Table 3 parameters")
+    groups = {}
+    for n in np.unique(count):
+        idx = np.flatnonzero(count == n)
+        n = int(n)
+        groups[n] = (idx, {k: np.ascontiguousarray(v[idx] if v.ndim == 1 else v[idx, :n]) for k, v in out.items()})
+    return groups

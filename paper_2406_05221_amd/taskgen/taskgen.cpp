@@ -158,3 +158,147 @@ extern "C" int taskgen_generate(uint64_t seed, uint64_t stream, uint64_t first_i
   }
   return 0;
 }
+
+namespace {
+
+/* Parameters of the schedulability experiments (Sec. 6.1, Table 3); ranges are inclusive. */
+struct Table3 {
+  uint64_t seed, stream, first_index;
+  uint32_t n_tasksets, n_cpus, per_cpu_lo, per_cpu_hi, max_gseg;
+  double gpu_ratio_lo, gpu_ratio_hi; /* share of GPU-using tasks in a taskset */
+  double util_lo, util_hi;           /* utilisation per CPU */
+  uint32_t t_lo, t_hi;               /* period, microseconds, drawn uniformly */
+  uint32_t eta_lo, eta_hi;           /* GPU segments of a GPU-using task */
+  double gc_lo, gc_hi;               /* G_i / C_i */
+  double gm_lo, gm_hi;               /* G^m_i / G_i */
+  uint32_t theta, eps, slice;
+};
+
+/* One taskset into row k of arrays laid out for n_max = n_cpus * per_cpu_hi tasks; the first
+ * count[k] slots of the row are the tasks (the rest is zero). */
+void one_table3(const Table3 &sp, const Out &o, uint32_t *count, uint32_t k) {
+  Rng rng(sp.seed, sp.stream, sp.first_index + k);
+  const uint32_t n_max = sp.n_cpus * sp.per_cpu_hi, S = sp.max_gseg;
+  const size_t to = (size_t)k * n_max;
+  o.theta[k] = sp.theta;
+  o.eps[k] = sp.eps;
+  o.slice[k] = sp.slice;
+  for (uint32_t i = 0; i < n_max; ++i) {
+    o.cpu[to + i] = o.period[to + i] = o.deadline[to + i] = 0;
+    o.prio[to + i] = 0;
+    o.core[to + i] = o.n_gseg[to + i] = 0;
+    for (uint32_t s = 0; s < S; ++s) o.gm[(to + i) * S + s] = o.ge[(to + i) * S + s] = 0;
+  }
+  /* number of tasks on each CPU, then the utilisation of each task: UUniFast per CPU */
+  std::vector<double> util;
+  for (uint32_t c = 0; c < sp.n_cpus; ++c) {
+    const uint32_t m = rng.integer(sp.per_cpu_lo, sp.per_cpu_hi);
+    double sum = rng.uniform(sp.util_lo, sp.util_hi);
+    for (uint32_t j = 0; j < m; ++j) {
+      double u = sum;
+      if (j + 1 < m) {
+        const double next = sum * std::pow(rng.uniform(), 1.0 / (double)(m - 1 - j));
+        u = sum - next;
+        sum = next;
+      }
+      util.push_back(u);
+    }
+  }
+  const uint32_t n = (uint32_t)util.size();
+  count[k] = n;
+  /* which tasks use the GPU: round(ratio * n) of them, chosen by a partial shuffle */
+  const double ratio = rng.uniform(sp.gpu_ratio_lo, sp.gpu_ratio_hi);
+  const uint32_t n_gpu = std::min(n, (uint32_t)std::floor(ratio * (double)n + 0.5));
+  std::vector<uint32_t> pick(n);
+  for (uint32_t i = 0; i < n; ++i) pick[i] = i;
+  std::vector<char> uses_gpu(n, 0);
+  for (uint32_t i = 0; i < n_gpu; ++i) {
+    std::swap(pick[i], pick[rng.integer(i, n - 1)]);
+    uses_gpu[pick[i]] = 1;
+  }
+  for (uint32_t i = 0; i < n; ++i) {
+    const uint32_t T = rng.integer(sp.t_lo, sp.t_hi);
+    const uint32_t eta = uses_gpu[i] ? rng.integer(sp.eta_lo, sp.eta_hi) : 0u;
+    uint32_t W = (uint32_t)std::floor(util[i] * (double)T + 0.5); /* C_i + G_i */
+    W = std::max(W, 2 * eta + 1);
+    uint32_t g = 0;
+    if (eta > 0) {
+      const double gc = rng.uniform(sp.gc_lo, sp.gc_hi);
+      g = (uint32_t)std::floor((double)W * gc / (1.0 + gc) + 0.5);
+      g = std::min(std::max(g, 2 * eta), W - 1);
+    }
+    const double gm_share = eta > 0 ? rng.uniform(sp.gm_lo, sp.gm_hi) : 0.0;
+    o.cpu[to + i] = W - g;
+    o.period[to + i] = T;
+    o.deadline[to + i] = T;
+    o.n_gseg[to + i] = (uint8_t)eta;
+    for (uint32_t s = 0; s < eta; ++s) {
+      const uint32_t gj = g / eta + (s < g % eta ? 1 : 0); /* >= 2 */
+      uint32_t m = (uint32_t)std::floor(gm_share * (double)gj + 0.5);
+      m = std::min(m, gj - 1);
+      o.gm[(to + i) * S + s] = m;
+      o.ge[(to + i) * S + s] = gj - m;
+    }
+  }
+  /* rate-monotonic priorities: shorter period = higher; equal periods: lower index higher */
+  for (uint32_t i = 0; i < n; ++i) {
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n; ++j)
+      if (o.period[to + j] < o.period[to + i] || (o.period[to + j] == o.period[to + i] && j < i)) ++rank;
+    o.prio[to + i] = (int32_t)(n - rank);
+  }
+  /* re-allocation to the CPUs, worst-fit decreasing: tasks by decreasing utilisation (ties: lower
+   * index first), each to the CPU with the smallest load so far (ties: lower CPU first) */
+  std::vector<uint32_t> by_util(n);
+  for (uint32_t i = 0; i < n; ++i) by_util[i] = i;
+  std::stable_sort(by_util.begin(), by_util.end(), [&](uint32_t a, uint32_t b) { return util[a] > util[b]; });
+  std::vector<double> load(sp.n_cpus, 0.0);
+  for (uint32_t i : by_util) {
+    uint32_t best = 0;
+    for (uint32_t c = 1; c < sp.n_cpus; ++c)
+      if (load[c] < load[best]) best = c;
+    o.core[to + i] = (uint8_t)best;
+    load[best] += util[i];
+  }
+}
+
+}  // namespace
+
+/*
+ * Tasksets by the recipe of the schedulability experiments (Sec. 6.1, Table 3).  Arrays are laid
+ * out for n_max = n_cpus * per_cpu_hi tasks per taskset; n_tasks[k] says how many of row k are
+ * tasks.  Returns 0, or -1 on invalid parameters.
+ */
+extern "C" int taskgen_table3(uint64_t seed, uint64_t stream, uint64_t first_index, uint32_t n_tasksets,
+                              uint32_t n_cpus, uint32_t per_cpu_lo, uint32_t per_cpu_hi, uint32_t max_gseg,
+                              double gpu_ratio_lo, double gpu_ratio_hi, double util_lo, double util_hi,
+                              uint32_t t_lo, uint32_t t_hi, uint32_t eta_lo, uint32_t eta_hi, double gc_lo,
+                              double gc_hi, double gm_lo, double gm_hi, uint32_t theta, uint32_t eps,
+                              uint32_t slice, int threads, uint32_t *n_tasks, uint32_t *theta_us,
+                              uint32_t *eps_us, uint32_t *slice_us, uint32_t *cpu_us, uint32_t *period_us,
+                              uint32_t *deadline_us, int32_t *prio, uint8_t *core, uint8_t *n_gseg,
+                              uint32_t *gm_us, uint32_t *ge_us) {
+  if (n_tasksets == 0 || n_cpus == 0 || n_cpus > 255 || per_cpu_lo == 0 || per_cpu_lo > per_cpu_hi ||
+      n_cpus * per_cpu_hi > 255 || eta_lo == 0 || eta_lo > eta_hi || eta_hi > max_gseg || t_lo == 0 || t_lo > t_hi ||
+      util_lo > util_hi || util_lo <= 0.0 || gpu_ratio_lo > gpu_ratio_hi || gpu_ratio_lo < 0.0 || gpu_ratio_hi > 1.0 ||
+      gc_lo > gc_hi || gc_lo < 0.0 || gm_lo > gm_hi || gm_lo < 0.0 || gm_hi > 1.0 || slice == 0)
+    return -1;
+  Table3 sp{seed, stream, first_index, n_tasksets, n_cpus, per_cpu_lo, per_cpu_hi, max_gseg, gpu_ratio_lo,
+            gpu_ratio_hi, util_lo, util_hi, t_lo, t_hi, eta_lo, eta_hi, gc_lo, gc_hi, gm_lo, gm_hi, theta, eps, slice};
+  Out o{theta_us, eps_us, slice_us, cpu_us, period_us, deadline_us, prio, core, n_gseg, gm_us, ge_us};
+  if (threads < 1) threads = 1;
+  if ((uint32_t)threads > n_tasksets) threads = (int)n_tasksets;
+  auto work = [&](int w) {
+    uint32_t lo = (uint32_t)((uint64_t)n_tasksets * w / threads);
+    uint32_t hi = (uint32_t)((uint64_t)n_tasksets * (w + 1) / threads);
+    for (uint32_t k = lo; k < hi; ++k) one_table3(sp, o, n_tasks, k);
+  };
+  if (threads == 1) {
+    work(0);
+  } else {
+    std::vector<std::thread> pool;
+    for (int w = 0; w < threads; ++w) pool.emplace_back(work, w);
+    for (auto &t : pool) t.join();
+  }
+  return 0;
+}

@@ -54,3 +54,45 @@ def test_any_taskset_can_be_regenerated_alone():
 def test_seed_changes_the_draw():
     a, b = taskgen.config(1, 50, seed=0), taskgen.config(1, 50, seed=1)
     assert (a["period_us"] != b["period_us"]).any()
+
+
+def test_table3_recipe_structure():
+    """Sec. 6.1 / Table 3: ranges, rate-monotonic priorities, worst-fit-decreasing allocation."""
+    groups = taskgen.table3(3000, seed=1)
+    assert sum(len(idx) for idx, _ in groups.values()) == 3000
+    assert min(groups) >= 12 and max(groups) <= 24 and len(groups) >= 10
+    seen = np.zeros(3000, bool)
+    for n, (idx, b) in groups.items():
+        assert not seen[idx].any()
+        seen[idx] = True
+        N = len(idx)
+        assert b["cpu_us"].shape == (N, n) and b["gm_us"].shape == (N, n, 3)
+        assert (b["theta_us"] == 200).all() and (b["eps_us"] == 1000).all() and (b["slice_us"] == 1024).all()
+        assert (b["period_us"] >= 30_000).all() and (b["period_us"] <= 500_000).all()
+        assert (b["deadline_us"] == b["period_us"]).all() and (b["core"] < 4).all()
+        gpu = b["n_gseg"] > 0
+        share = gpu.mean(axis=1)
+        assert (share >= 0.4 - 0.5 / n - 1e-9).all() and (share <= 0.6 + 0.5 / n + 1e-9).all()
+        assert (b["n_gseg"][gpu] >= 1).all() and (b["n_gseg"][gpu] <= 3).all()
+        used = np.arange(3)[None, None, :] < b["n_gseg"][:, :, None]
+        assert (b["gm_us"][~used] == 0).all() and (b["ge_us"][~used] == 0).all() and (b["ge_us"][used] >= 1).all()
+        Gm, Ge = b["gm_us"].sum(axis=2).astype(float), b["ge_us"].sum(axis=2).astype(float)
+        G, C = Gm + Ge, b["cpu_us"].astype(float)
+        big = gpu & (G + C > 2000)  # rounding to whole microseconds matters for tiny tasks only
+        assert (G[big] / C[big] > 0.19).all() and (G[big] / C[big] < 2.05).all()
+        assert (Gm[big] / G[big] > 0.09).all() and (Gm[big] / G[big] < 0.31).all()
+        assert (np.sort(b["prio"], axis=1) == np.arange(1, n + 1)).all()
+        order = np.argsort(-b["prio"], axis=1)
+        assert (np.diff(np.take_along_axis(b["period_us"], order, 1).astype(np.int64), axis=1) >= 0).all()
+        # total utilisation: 4 CPUs x [0.4, 0.6]; worst-fit decreasing leaves the CPUs balanced: no CPU
+        # exceeds the lightest one by more than the largest task placed after it, i.e. by more than its own
+        # smallest task would explain; the cheap check: max - min load <= largest task utilisation
+        u = (C + G) / b["period_us"]
+        assert (u.sum(axis=1) > 1.55).all() and (u.sum(axis=1) < 2.45).all()
+        load = np.stack([(u * (b["core"] == c)).sum(axis=1) for c in range(4)], axis=1)
+        assert (load.max(axis=1) - load.min(axis=1) <= u.max(axis=1) + 1e-3).all()
+    assert seen.all()
+    again = taskgen.table3(3000, seed=1, threads=3)
+    assert all((again[n][1]["cpu_us"] == groups[n][1]["cpu_us"]).all() for n in groups)
+    one = taskgen.table3(50, seed=1, util=(0.5, 0.5), tasks_per_cpu=(4, 4))
+    assert list(one) == [16]
