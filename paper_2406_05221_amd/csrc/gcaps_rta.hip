@@ -231,8 +231,8 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
    * workgroup's first tile is its own index, so one that had to wait for a free slot would start
    * that tile only after the others have drained the queue. */
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fast::rta_deep_kernel<BUSY, Q, CONT>, 64, lds) != hipSuccess ||
-      per_cu < 1) {
+  const void *fn = (const void *)fast::rta_deep_kernel<BUSY, Q, CONT>;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
     (void)hipGetLastError();
     per_cu = 1;
   }
@@ -406,8 +406,11 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
     /* second launch: the search, persistent workgroups over the list */
     const bool busy = wait_mode == GCAPS_WAIT_BUSY;
     const size_t lds = gprio::gprio_lds_bytes(n);
-    const void *fn = n <= 20 ? (busy ? (const void *)gprio::gprio_fast_kernel<true, 5> : (const void *)gprio::gprio_fast_kernel<false, 5>)
-                             : (busy ? (const void *)gprio::gprio_fast_kernel<true, 8> : (const void *)gprio::gprio_fast_kernel<false, 8>);
+    const void *fn5 = busy ? (const void *)gprio::gprio_fast_kernel<true, 5>
+                           : (const void *)gprio::gprio_fast_kernel<false, 5>;
+    const void *fn8 = busy ? (const void *)gprio::gprio_fast_kernel<true, 8>
+                           : (const void *)gprio::gprio_fast_kernel<false, 8>;
+    const void *fn = n <= 20 ? fn5 : fn8;
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
       (void)hipGetLastError();

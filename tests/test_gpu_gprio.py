@@ -193,3 +193,24 @@ def test_full_size_workloads_device_entry(oracle, gpu, k, first, N):
         assert (np.sort(got_g[found], axis=1) == np.arange(1, n + 1)).all()
         assert (got_r[found] <= batch["deadline_us"][found]).all() and (got_r[found] > 0).all()
         assert (got_g[~found] == 0).all() and (got_r[~found] == -2).all()
+
+
+def test_maximum_shapes(oracle, gpu):
+    """255 GPU segments per task; 255 tasks per taskset (the general kernel); 32 tasks (the widest the quad-lane
+    kernel takes) and 33 (the narrowest it does not)."""
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(8)
+    batch = taskgen.generate(40, n_cores=2, tasks_per_core=1, max_gseg=255, util=(0.2, 0.5), eta=(0, 255),
+                             share=(0.3, 0.6), period=(200_000, 1_000_000), overhead=(0, 3), slice_us=64, seed=2,
+                             stream=90)
+    assert compare(oracle, B, ctx, batch) > 0
+    batch = relaxed_workload(33, seed=4, n_cores=5, per_core=51, S=1)
+    compare(oracle, B, ctx, batch)
+    for per_core, wide in ((8, 0), (11, 64)):  # 4 x 8 = 32 tasks, 3 x 11 = 33 tasks
+        cores = 4 if per_core == 8 else 3
+        batch = taskgen.generate(64, n_cores=cores, tasks_per_core=per_core, max_gseg=2, util=(0.1, 0.4), eta=(0, 2),
+                                 share=(0.05, 0.4), period=(50_000, 1_000_000), overhead=(0, 20), slice_us=1024,
+                                 seed=int(rng.integers(1, 99)), stream=91)
+        assert compare(oracle, B, ctx, batch) > 0
+        assert B.gcaps_last_wide_count(ctx) == wide
