@@ -7,7 +7,14 @@ Columns: the default round-robin TSG scheduling (Sec. 5.2) and GCAPS (Sec. 5.3),
 busy-waiting and self-suspension, and GCAPS with the GPU-segment priority assignment tried for the
 tasksets that fail with equal priorities (Sec. 4.3 / 5.4, the procedure of Sec. 6.1).  Everything
 is computed by the GPU library; this module only draws inputs, groups them by task count (a batch
-of the library has one task count) and averages verdicts."""
+of the library has one task count) and averages verdicts.
+
+Best-effort tasks (``--param be_ratio``, the last experiment of Sec. 6.1) run below every real-time
+task and have no deadline.  Under round-robin TSG scheduling their GPU segments take part in the time
+slicing: they stay in the taskset (Eq. 3 and Lemma 4 count every GPU-using task) and only the
+real-time tasks' bounds decide the verdict.  Under GCAPS a lower-priority task can delay a real-time
+task by the runlist-update blocking of Lemma 8 only, which is charged to every task anyway: the
+best-effort tasks are left out of the taskset."""
 import argparse
 
 import numpy as np
@@ -24,23 +31,36 @@ def verdicts(ctx, groups):
     total = sum(len(idx) for idx, _ in groups.values())
     out = {c: np.zeros(total, np.uint8) for c in COLUMNS}
     for idx, batch in groups.values():
+        be = batch.get("best_effort")
+        fields = {k: v for k, v in batch.items() if k != "best_effort"}
+        real_time = fields if be is None else taskgen.without_tasks(fields, be != 0)
         for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
-            _, sched = B.gcaps_rta_batch(ctx, batch, B.GCAPS_POLICY_BOTH, wait)
-            out[f"gcaps_{name}"][idx] = sched[0]
-            out[f"tsg_rr_{name}"][idx] = sched[1]
+            if be is None:
+                _, sched = B.gcaps_rta_batch(ctx, fields, B.GCAPS_POLICY_BOTH, wait)
+                gcaps, rr = sched[0], sched[1]
+            else:
+                # round-robin: best-effort tasks stay (lowest priorities: they are analysed last and a miss
+                # among them ends nothing above them); the verdict is that of the real-time tasks
+                resp, _ = B.gcaps_rta_batch(ctx, fields, B.GCAPS_POLICY_RR, wait)
+                rr = ((resp[0] >= 0) | (be != 0)).all(axis=1).astype(np.uint8)
+                _, sched = B.gcaps_rta_batch(ctx, real_time, B.GCAPS_POLICY_GCAPS, wait)
+                gcaps = sched[0]
+            out[f"gcaps_{name}"][idx] = gcaps
+            out[f"tsg_rr_{name}"][idx] = rr
             # separate GPU-segment priorities only where the test with equal priorities failed
-            _, _, found = B.gcaps_gprio_assign_batch(ctx, batch, wait, skip=sched[0])
+            _, _, found = B.gcaps_gprio_assign_batch(ctx, real_time, wait, skip=gcaps)
             out[f"gcaps_{name}+prio"][idx] = found
     return out
 
 
-def sweep(ctx, param, values, n_tasksets, seed=0):
+def sweep(ctx, param, values, n_tasksets, seed=0, **fixed):
     """One row per value of `param` (a key of ``taskgen.TABLE3``; range parameters are set to the
-    single value): the share of schedulable tasksets per column."""
+    single value): the share of schedulable tasksets per column.  `fixed`: other Table 3 parameters
+    to hold at values of the caller's choice."""
     rows = []
     for k, v in enumerate(values):
         value = (v, v) if isinstance(taskgen.TABLE3[param], tuple) else v
-        groups = taskgen.table3(n_tasksets, seed=seed, stream=300 + k, **{param: value})
+        groups = taskgen.table3(n_tasksets, seed=seed, stream=300 + k, **{**fixed, param: value})
         res = verdicts(ctx, groups)
         rows.append((v, {c: float(res[c].mean()) for c in COLUMNS}))
     return rows
@@ -52,13 +72,20 @@ def main():
     ap.add_argument("--values", default="0.2,0.3,0.4,0.5,0.6,0.7")
     ap.add_argument("--tasksets", type=int, default=1000, help="tasksets per point (the paper uses 1,000)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--util", type=float, default=None, help="hold the utilisation per CPU at this value")
+    ap.add_argument("--eps-us", type=int, default=None, help="hold the runlist-update delay at this value")
     args = ap.parse_args()
     cast = int if isinstance(taskgen.TABLE3[args.param], int) or args.param in ("tasks_per_cpu", "period", "eta") \
         else float
     values = [cast(x) for x in args.values.split(",")]
     ctx = B.gcaps_create(0)
     try:
-        rows = sweep(ctx, args.param, values, args.tasksets, args.seed)
+        fixed = {}
+        if args.util is not None and args.param != "util":
+            fixed["util"] = (args.util, args.util)
+        if args.eps_us is not None and args.param != "eps_us":
+            fixed["eps_us"] = args.eps_us
+        rows = sweep(ctx, args.param, values, args.tasksets, args.seed, **fixed)
     finally:
         B.gcaps_destroy(ctx)
     print(f"| {args.param} | " + " | ".join(COLUMNS) + " |")

@@ -127,7 +127,8 @@ def config(k, n_tasksets=None, *, first_index=0, seed=0, threads=None):
 
 # ---- the recipe of the paper's schedulability experiments (Sec. 6.1, Table 3) ---------------------
 TABLE3 = dict(n_cpus=4, tasks_per_cpu=(3, 6), gpu_ratio=(0.4, 0.6), util=(0.4, 0.6), period=(30_000, 500_000),
-              eta=(1, 3), g_over_c=(0.2, 2.0), gm_over_g=(0.1, 0.3), theta_us=200, eps_us=1000, slice_us=1024)
+              eta=(1, 3), g_over_c=(0.2, 2.0), gm_over_g=(0.1, 0.3), theta_us=200, eps_us=1000, slice_us=1024,
+              be_ratio=0.0)
 
 
 def table3(n_tasksets, *, seed=0, stream=300, first_index=0, threads=None, **overrides):
@@ -138,7 +139,13 @@ def table3(n_tasksets, *, seed=0, stream=300, first_index=0, threads=None, **ove
 
     Tasksets differ in their number of tasks, a batch of the library does not: the result is a dict
     {n: (indices, batch)} with one batch per task count n, `indices` saying which of the generated
-    tasksets (in generation order) the rows of the batch are."""
+    tasksets (in generation order) the rows of the batch are.
+
+    be_ratio > 0 (the last experiment of Sec. 6.1): round(be_ratio * n) tasks of every taskset, chosen
+    at random, are best-effort tasks.  They run below every real-time task (their priorities are
+    moved below, keeping their order) and have no deadline to test; each batch then also holds
+    ``best_effort`` (uint8 [N, n], not part of the library's task model: see ``sweep.py`` for how
+    the analyses treat such tasks)."""
     q = dict(TABLE3)
     unknown = set(overrides) - set(q)
     if unknown:
@@ -164,9 +171,38 @@ def table3(n_tasksets, *, seed=0, stream=300, first_index=0, threads=None, **ove
                                                                       "n_gseg", "gm_us", "ge_us")])
     if rc != 0:
         raise ValueError("taskgen: invalid Table 3 parameters")
+    be = float(q["be_ratio"])
+    if not 0.0 <= be <= 1.0:
+        raise ValueError("be_ratio must be within [0, 1]")
     groups = {}
     for n in np.unique(count):
         idx = np.flatnonzero(count == n)
         n = int(n)
-        groups[n] = (idx, {k: np.ascontiguousarray(v[idx] if v.ndim == 1 else v[idx, :n]) for k, v in out.items()})
+        batch = {k: np.ascontiguousarray(v[idx] if v.ndim == 1 else v[idx, :n]) for k, v in out.items()}
+        if be > 0.0:
+            rng = np.random.default_rng([seed, stream, 7, n])
+            order = np.argsort(rng.random((len(idx), n)), axis=1)
+            chosen = np.zeros((len(idx), n), bool)
+            np.put_along_axis(chosen, order[:, :int(np.floor(be * n + 0.5))], True, axis=1)
+            batch["best_effort"] = chosen.astype(np.uint8)
+            batch["prio"] = np.where(chosen, batch["prio"] - n, batch["prio"]).astype(np.int32)
+        groups[n] = (idx, batch)
     return groups
+
+
+def without_tasks(batch, drop):
+    """The batch with the tasks marked in `drop` (bool [N, n], the same number per taskset) removed."""
+    N, n = batch["cpu_us"].shape
+    keep = ~np.asarray(drop, bool)
+    m = int(keep[0].sum())
+    assert (keep.sum(axis=1) == m).all()
+    sel = np.argsort(~keep, axis=1, kind="stable")[:, :m]  # kept tasks in their order
+    out = {}
+    for k, v in batch.items():
+        if v.ndim == 1:
+            out[k] = v
+        elif v.ndim == 2:
+            out[k] = np.ascontiguousarray(np.take_along_axis(v, sel, axis=1))
+        else:
+            out[k] = np.ascontiguousarray(np.take_along_axis(v, sel[:, :, None], axis=1))
+    return out

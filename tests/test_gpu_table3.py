@@ -15,12 +15,23 @@ def oracle_verdicts(oracle, groups):
     total = sum(len(idx) for idx, _ in groups.values())
     cols = ["tsg_rr_busy", "tsg_rr_suspend", "gcaps_busy", "gcaps_suspend", "gcaps_busy+prio", "gcaps_suspend+prio"]
     out = {c: np.zeros(total, np.uint8) for c in cols}
+    from paper_2406_05221_amd import taskgen
     for idx, batch in groups.values():
+        be = batch.get("best_effort")
+        fields = {k: v for k, v in batch.items() if k != "best_effort"}
         for wait, name in ((BUSY, "busy"), (SUSPEND, "suspend")):
-            _, sched, _ = oracle.rta_batch(batch, BOTH, wait, threads=16)
-            out[f"gcaps_{name}"][idx] = sched[0]
-            out[f"tsg_rr_{name}"][idx] = sched[1]
-            out[f"gcaps_{name}+prio"][idx] = oracle.gprio_assign_batch(batch, wait, skip=sched[0], threads=16)[2]
+            if be is None:
+                _, sched, _ = oracle.rta_batch(fields, BOTH, wait, threads=16)
+                gcaps, rr, real_time = sched[0], sched[1], fields
+            else:
+                # best-effort tasks: in the round-robin taskset but untested; not in the GCAPS taskset
+                resp, _, _ = oracle.rta_batch(fields, RR, wait, threads=16)
+                rr = np.array([all(r >= 0 for r, b in zip(row, flags) if not b) for row, flags in zip(resp[0], be)])
+                real_time = taskgen.without_tasks(fields, be != 0)
+                gcaps = oracle.rta_batch(real_time, GCAPS, wait, threads=16)[1][0]
+            out[f"gcaps_{name}"][idx] = gcaps
+            out[f"tsg_rr_{name}"][idx] = rr
+            out[f"gcaps_{name}+prio"][idx] = oracle.gprio_assign_batch(real_time, wait, skip=gcaps, threads=16)[2]
     return out
 
 
@@ -58,3 +69,18 @@ def test_sweep_matches_the_oracle(oracle, gpu):
     for _, shares in rows:
         assert shares["gcaps_busy+prio"] >= shares["gcaps_busy"]
         assert shares["gcaps_suspend+prio"] >= shares["gcaps_suspend"]
+
+
+def test_sweep_with_best_effort_tasks_matches_the_oracle(oracle, gpu):
+    from paper_2406_05221_amd import sweep, taskgen
+    B, ctx, _ = gpu
+    rows = sweep.sweep(ctx, "be_ratio", [0.0, 0.3], 600, seed=6, util=(0.45, 0.45))
+    for k, (value, shares) in enumerate(rows):
+        groups = taskgen.table3(600, seed=6, stream=300 + k, be_ratio=value, util=(0.45, 0.45))
+        want = oracle_verdicts(oracle, groups)
+        for c in sweep.COLUMNS:
+            assert shares[c] == float(want[c].mean()), (value, c)
+    # turning tasks into best-effort ones helps GCAPS (they no longer preempt anyone) more than round-robin
+    # (their GPU segments still take their time slices)
+    gain = {c: rows[1][1][c] - rows[0][1][c] for c in sweep.COLUMNS}
+    assert gain["gcaps_suspend"] > 0 and gain["gcaps_busy"] > 0

@@ -96,3 +96,21 @@ def test_table3_recipe_structure():
     assert all((again[n][1]["cpu_us"] == groups[n][1]["cpu_us"]).all() for n in groups)
     one = taskgen.table3(50, seed=1, util=(0.5, 0.5), tasks_per_cpu=(4, 4))
     assert list(one) == [16]
+
+
+def test_table3_best_effort_tasks():
+    groups = taskgen.table3(800, seed=2, be_ratio=0.25)
+    for n, (idx, b) in groups.items():
+        be = b["best_effort"] != 0
+        assert (be.sum(axis=1) == int(np.floor(0.25 * n + 0.5))).all()
+        # below every real-time task, order among themselves and among the real-time tasks kept
+        assert (np.where(be, b["prio"], -10**9).max(axis=1) < np.where(~be, b["prio"], 10**9).min(axis=1)).all()
+        plain = taskgen.table3(800, seed=2)[n][1]
+        assert (np.where(be, b["prio"] + n, b["prio"]) == plain["prio"]).all()
+        assert all((b[k] == plain[k]).all() for k in plain if k != "prio")
+        rt = taskgen.without_tasks({k: v for k, v in b.items() if k != "best_effort"}, be)
+        m = n - int(be[0].sum())
+        assert rt["cpu_us"].shape == (len(idx), m) and rt["ge_us"].shape == (len(idx), m, 3)
+        last = len(idx) - 1
+        assert (rt["cpu_us"][0] == b["cpu_us"][0][~be[0]]).all() and (rt["gm_us"][last] == b["gm_us"][last][~be[last]]).all()
+        assert (rt["eps_us"] == b["eps_us"]).all()
