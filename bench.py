@@ -27,8 +27,8 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="a2bdc866fe6ce95e68ed984cf69dfb5affe897ae211f4ba2cfb27fae75282186",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943833963, write_bytes=333290176)
+MEASURED_TRAFFIC = dict(csrc_sha256="73c92de895e021d14c70a2408ea787e51adfaab3c58ebe527376a32ad77456f8",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943834379, write_bytes=333289931)
 
 
 def csrc_sha256():

@@ -79,7 +79,8 @@ enum { GCAPS_WAIT_BUSY = 0, GCAPS_WAIT_SUSPEND = 1 };
 enum {
   GCAPS_OK = 0,
   GCAPS_EINVAL = -1,  /* null pointer, zero or out-of-range size, unknown selector */
-  GCAPS_ETASK = -2,   /* a taskset violates the task model: T = 0, D = 0, D > T, L = 0, eta^g > S */
+  GCAPS_ETASK = -2,   /* a taskset violates the task model: T = 0, D = 0, D > T, L = 0, eta^g > S
+                         (gcaps_gprio_rta_batch: or its GPU priorities disagree with prio on a core) */
   GCAPS_ENOMEM = -3,  /* host or device allocation failed */
   GCAPS_EDEVICE = -4  /* a HIP call failed (no device, launch failure, ...) */
 };
@@ -184,6 +185,26 @@ int gcaps_gprio_assign_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_
 int gcaps_gprio_assign_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode,
                                     const uint8_t *d_skip, int32_t *d_out_gprio, int64_t *d_out_resp,
                                     uint8_t *d_out_sched);
+
+/*
+ * The analysis of Sec. 5.4 for GPU-segment priorities GIVEN by the caller, under GCAPS: the bound
+ * of every task with the sums over higher-priority tasks of other cores (second sums of Lemmas 10
+ * and 13, Lemma 11) taken over the tasks with a higher GPU priority, and D_h in place of R_h in
+ * every jitter (not taken below zero).  The tasks do not depend on each other's bounds: every task
+ * is analysed.
+ *   gprio      int32 [n_tasksets][n_tasks], caller order: larger = higher GPU priority; equal
+ *              values are ordered by CPU priority.  Two tasks of one core ordered differently by
+ *              prio and gprio make the taskset invalid (Sec. 4.3: such an order may deadlock);
+ *              it is reported like a task-model violation (GCAPS_ETASK, smallest index)
+ *   out_resp   int64 [n_tasksets][n_tasks]: R_i, or GCAPS_RESP_MISS where the bound exceeds D_i
+ *   out_sched  uint8 [n_tasksets]: 1 iff no task missed
+ * Runs in the general 64-bit kernel (one lane per taskset).  Host / device variants and error
+ * reporting as for gcaps_gprio_assign_batch[_device].
+ */
+int gcaps_gprio_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode, const int32_t *gprio,
+                          int64_t *out_resp, uint8_t *out_sched, uint32_t *first_bad_taskset);
+int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode, const int32_t *d_gprio,
+                                 int64_t *d_out_resp, uint8_t *d_out_sched);
 
 /*
  * Optional ordering (off by default) of the tasksets that need the second,

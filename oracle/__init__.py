@@ -54,6 +54,8 @@ def _open(path):
                                      i32, i32, u32, i32, p, p, p, p]
     lib.oracle_gprio_rta_taskset.restype = ctypes.c_int
     lib.oracle_gprio_rta_taskset.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, i32, u32, p, p, p]
+    lib.oracle_gprio_rta_batch.restype = ctypes.c_int
+    lib.oracle_gprio_rta_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, i32, u32, p, p, p]
     lib.oracle_gprio_assign_taskset.restype = ctypes.c_int
     lib.oracle_gprio_assign_taskset.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, i32, u32, p, p, p, p]
     lib.oracle_gprio_assign_batch.restype = ctypes.c_int
@@ -239,3 +241,27 @@ def gprio_assign_batch(batch, wait_mode, *, skip=None, options=0, threads=1, lib
     if rc != OK:
         raise OracleError(rc, int(bad[0]))
     return gp, resp, sched, int(terms[0])
+
+
+def gprio_rta_batch(batch, gprio, wait_mode, *, options=0, lib=None):
+    """Sec. 5.4 for given GPU-segment priorities over a batch (dict as for rta_batch; gprio int32 [N, n]).
+    Returns (resp[N, n] int64, sched[N] uint8)."""
+    cpu = _arr(batch["cpu_us"], np.uint32)
+    N, n = cpu.shape
+    gm = _arr(batch["gm_us"], np.uint32).reshape(N, n, -1)
+    ge = _arr(batch["ge_us"], np.uint32).reshape(N, n, -1)
+    S = gm.shape[2]
+    ep = _arr(batch["eps_us"], np.uint32)
+    per, dl = _arr(batch["period_us"], np.uint32), _arr(batch["deadline_us"], np.uint32)
+    pr, co, ng = _arr(batch["prio"], np.int32), _arr(batch["core"], np.uint8), _arr(batch["n_gseg"], np.uint8)
+    gp = _arr(gprio, np.int32)
+    assert gp.shape == (N, n) and ep.shape == (N,)
+    resp = np.zeros((N, n), np.int64)
+    sched = np.zeros(N, np.uint8)
+    bad = np.full(1, 0xFFFFFFFF, np.uint32)
+    rc = (lib or _load()).oracle_gprio_rta_batch(N, n, S, _ptr(ep), _ptr(cpu), _ptr(per), _ptr(dl), _ptr(pr), _ptr(co),
+                                                 _ptr(ng), _ptr(gm), _ptr(ge), _ptr(gp), wait_mode, options,
+                                                 _ptr(resp), _ptr(sched), _ptr(bad))
+    if rc != OK:
+        raise OracleError(rc, int(bad[0]))
+    return resp, sched

@@ -599,3 +599,26 @@ extern "C" int oracle_gprio_assign_batch(uint32_t n_tasksets, uint32_t n_tasks, 
   if (terms_total) *terms_total = total;
   return ORACLE_OK;
 }
+
+extern "C" int oracle_gprio_rta_batch(uint32_t n_tasksets, uint32_t n_tasks, uint32_t max_gseg,
+                                      const uint32_t *eps_us, const uint32_t *cpu_us,
+                                      const uint32_t *period_us, const uint32_t *deadline_us,
+                                      const int32_t *prio, const uint8_t *core, const uint8_t *n_gseg,
+                                      const uint32_t *gm_us, const uint32_t *ge_us, const int32_t *gprio,
+                                      int wait_mode, uint32_t options, int64_t *resp, uint8_t *sched,
+                                      uint32_t *first_bad) {
+  if (n_tasksets == 0 || !eps_us || !gprio || !resp || !sched) return ORACLE_EINVAL;
+  for (uint32_t s = 0; s < n_tasksets; ++s) {
+    size_t to = (size_t)s * n_tasks;
+    size_t so = to * max_gseg;
+    int r = oracle_gprio_rta_taskset(n_tasks, max_gseg, eps_us[s], cpu_us + to, period_us + to,
+                                     deadline_us + to, prio + to, core + to, n_gseg + to,
+                                     gm_us ? gm_us + so : nullptr, ge_us ? ge_us + so : nullptr, gprio + to,
+                                     wait_mode, options, resp + to, sched + s, nullptr);
+    if (r != ORACLE_OK) {
+      if (first_bad) *first_bad = s;
+      return r;
+    }
+  }
+  return ORACLE_OK;
+}

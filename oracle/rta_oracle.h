@@ -120,6 +120,14 @@ int oracle_gprio_rta_taskset(uint32_t n_tasks, uint32_t max_gseg, uint32_t eps_u
                              const int32_t *gprio, int wait_mode, uint32_t options, int64_t *resp,
                              uint8_t *sched, uint64_t *terms);
 
+/* The same for every taskset of a batch (gprio and resp [n_tasksets*n_tasks], sched [n_tasksets]);
+ * stops at the first taskset that is invalid or whose priorities disagree on a core (*first_bad). */
+int oracle_gprio_rta_batch(uint32_t n_tasksets, uint32_t n_tasks, uint32_t max_gseg, const uint32_t *eps_us,
+                           const uint32_t *cpu_us, const uint32_t *period_us, const uint32_t *deadline_us,
+                           const int32_t *prio, const uint8_t *core, const uint8_t *n_gseg,
+                           const uint32_t *gm_us, const uint32_t *ge_us, const int32_t *gprio, int wait_mode,
+                           uint32_t options, int64_t *resp, uint8_t *sched, uint32_t *first_bad);
+
 /*
  * Sec. 4.3: search for GPU-segment priorities by Audsley's scheme.  Levels are handed out
  * from the lowest (1) to the highest (n).  At each level the unassigned tasks are tried from

@@ -25,7 +25,8 @@ GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
-           "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss"]
+           "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
+           "gcaps_gprio_rta_batch_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -55,6 +56,10 @@ _lib.gcaps_gprio_assign_batch.restype = _int
 _lib.gcaps_gprio_assign_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p, ctypes.POINTER(_u32)]
 _lib.gcaps_gprio_assign_batch_device.restype = _int
 _lib.gcaps_gprio_assign_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, _p]
+_lib.gcaps_gprio_rta_batch.restype = _int
+_lib.gcaps_gprio_rta_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p, ctypes.POINTER(_u32)]
+_lib.gcaps_gprio_rta_batch_device.restype = _int
+_lib.gcaps_gprio_rta_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _p, _p, _p]
 _lib.gcaps_set_continue_after_miss.restype = _int
 _lib.gcaps_set_continue_after_miss.argtypes = [_p, _int]
 _lib.gcaps_strerror.restype = ctypes.c_char_p
@@ -226,5 +231,45 @@ def gcaps_gprio_assign_batch_device(ctx, dbatch, wait_mode, d_skip, d_gprio, d_r
     rc = _lib.gcaps_gprio_assign_batch_device(ctx, ctypes.byref(b), wait_mode,
                                               d_skip.data_ptr() if d_skip is not None else None,
                                               d_gprio.data_ptr(), d_resp.data_ptr(), d_sched.data_ptr())
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+
+
+def gcaps_gprio_rta_batch(ctx, batch, wait_mode, gprio):
+    """Host entry point of the analysis for given GPU-segment priorities (int32 [N, n]).
+    Returns (resp int64 [N, n], sched uint8 [N])."""
+    N, n, S = _shape(batch)
+    keep = {}
+    b = gcaps_batch(n_tasksets=N, n_tasks=n, max_gseg=S)
+    for name, dtype, ndim in _FIELDS:
+        a = np.ascontiguousarray(batch[name], dtype=dtype)
+        assert a.ndim == ndim and a.shape[0] == N, name
+        keep[name] = a
+        setattr(b, name, a.ctypes.data if a.size else None)
+    gp = np.ascontiguousarray(gprio, dtype=np.int32)
+    assert gp.shape == (N, n)
+    resp = np.empty((N, n), np.int64)
+    sched = np.empty(N, np.uint8)
+    bad = _u32(0xFFFFFFFF)
+    rc = _lib.gcaps_gprio_rta_batch(ctx, ctypes.byref(b), wait_mode, gp.ctypes.data, resp.ctypes.data,
+                                    sched.ctypes.data, ctypes.byref(bad))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)
+    return resp, sched
+
+
+def gcaps_gprio_rta_batch_device(ctx, dbatch, wait_mode, d_gprio, d_resp, d_sched):
+    """Device entry point of the analysis for given GPU-segment priorities."""
+    N, n = dbatch["cpu_us"].shape
+    S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
+    b = gcaps_batch(n_tasksets=int(N), n_tasks=int(n), max_gseg=int(S))
+    for name, _, _ in _FIELDS:
+        t = dbatch[name]
+        assert t.is_cuda and t.is_contiguous(), name
+        setattr(b, name, t.data_ptr() if t.numel() else None)
+    for t, count, size in ((d_gprio, N * n, 4), (d_resp, N * n, 8), (d_sched, N, 1)):
+        assert t.is_cuda and t.is_contiguous() and t.numel() == count and t.element_size() == size
+    rc = _lib.gcaps_gprio_rta_batch_device(ctx, ctypes.byref(b), wait_mode, d_gprio.data_ptr(), d_resp.data_ptr(),
+                                           d_sched.data_ptr())
     if rc != GCAPS_OK:
         raise GcapsError(rc)

@@ -452,6 +452,25 @@ int run_gprio(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const uint8_t
   });
 }
 
+/* Sec. 5.4 for given GPU priorities: the general kernel over every taskset of the chunk */
+int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const int32_t *d_gprio, int64_t *d_resp,
+                    uint8_t *d_sched) {
+  const u64 n = b->n_tasks;
+  return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
+    hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr, c0 == 0 ? 1 : 0);
+    if (hipGetLastError() != hipSuccess) return (int)GCAPS_EDEVICE;
+    ctx->wide_only = true;
+    const u32 slots = wide_slots(ctx, sub->n_tasksets);
+    wide::Scratch ws;
+    int rc = wide_columns(ctx, sub->n_tasks, slots, &ws);
+    if (rc != GCAPS_OK) return rc;
+    hipLaunchKernelGGL(gprio::gprio_given_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *sub, wait_mode,
+                       (const int *)(d_gprio + c0 * n), (long long *)(d_resp + c0 * n), d_sched + c0,
+                       (u32 *)ctx->status.ptr, ws, ctx->ts_offset);
+    return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
+  });
+}
+
 int check_gprio_batch(const gcaps_batch *b, int wait_mode, const void *gprio, const void *resp, const void *sched) {
   if (!b || !gprio || !resp || !sched) return GCAPS_EINVAL;
   if (b->n_tasksets == 0 || b->n_tasks == 0 || b->n_tasks > 255 || b->max_gseg > 255) return GCAPS_EINVAL;
@@ -718,11 +737,57 @@ extern "C" int gcaps_gprio_assign_batch(gcaps_ctx *ctx, const gcaps_batch *batch
   return GCAPS_OK;
 }
 
+extern "C" int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode,
+                                            const int32_t *d_gprio, int64_t *d_out_resp, uint8_t *d_out_sched) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_gprio_batch(batch, wait_mode, d_gprio, d_out_resp, d_out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  return run_gprio_given(ctx, batch, wait_mode, d_gprio, d_out_resp, d_out_sched);
+}
+
+extern "C" int gcaps_gprio_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode, const int32_t *gprio,
+                                     int64_t *out_resp, uint8_t *out_sched, uint32_t *first_bad_taskset) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_gprio_batch(batch, wait_mode, gprio, out_resp, out_sched);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  const size_t N = batch->n_tasksets, n = batch->n_tasks;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t resp_bytes = up(N * n * 8), gprio_bytes = up(N * n * 4), sched_bytes = up(N);
+  gcaps_batch d;
+  rc = upload_batch(ctx, batch, &d, nullptr, nullptr);
+  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(resp_bytes + gprio_bytes + sched_bytes);
+  if (rc != GCAPS_OK) return rc;
+  int64_t *d_resp = (int64_t *)ctx->staging_out.ptr;
+  int32_t *d_gprio = (int32_t *)((char *)ctx->staging_out.ptr + resp_bytes);
+  uint8_t *d_sched = (uint8_t *)ctx->staging_out.ptr + resp_bytes + gprio_bytes;
+  if (hipMemcpyAsync(d_gprio, gprio, N * n * 4, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  rc = run_gprio_given(ctx, &d, wait_mode, d_gprio, d_resp, d_sched);
+  if (rc != GCAPS_OK) return rc;
+  rc = gcaps_status(ctx, first_bad_taskset);
+  if (rc != GCAPS_OK) return rc;
+  if (hipMemcpyAsync(out_resp, d_resp, N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_sched, d_sched, N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  return GCAPS_OK;
+}
+
 extern "C" const char *gcaps_strerror(int code) {
   switch (code) {
     case GCAPS_OK: return "success";
     case GCAPS_EINVAL: return "invalid argument (null pointer, size out of range or unknown selector)";
-    case GCAPS_ETASK: return "a taskset violates the task model (T = 0, D = 0, D > T, L = 0 or eta^g > S)";
+    case GCAPS_ETASK:
+      return "a taskset violates the task model (T = 0, D = 0, D > T, L = 0, eta^g > S, or GPU priorities that "
+             "disagree with the CPU priorities on a core)";
     case GCAPS_ENOMEM: return "host or device allocation failed";
     case GCAPS_EDEVICE: return "a HIP runtime call failed";
     default: return "unknown gcaps error code";

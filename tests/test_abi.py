@@ -50,6 +50,8 @@ def test_argument_errors_need_no_device(binding):
     assert lib.gcaps_last_wide_count(None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_gprio_assign_batch(None, None, 0, None, None, None, None, None) == binding.GCAPS_EINVAL
     assert lib.gcaps_gprio_assign_batch_device(None, None, 0, None, None, None, None) == binding.GCAPS_EINVAL
+    assert lib.gcaps_gprio_rta_batch(None, None, 0, None, None, None, None) == binding.GCAPS_EINVAL
+    assert lib.gcaps_gprio_rta_batch_device(None, None, 0, None, None, None) == binding.GCAPS_EINVAL
     lib.gcaps_destroy.argtypes = [ctypes.c_void_p]
     lib.gcaps_destroy(None)
 

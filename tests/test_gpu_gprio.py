@@ -214,3 +214,99 @@ def test_maximum_shapes(oracle, gpu):
                                  seed=int(rng.integers(1, 99)), stream=91)
         assert compare(oracle, B, ctx, batch) > 0
         assert B.gcaps_last_wide_count(ctx) == wide
+
+
+# ---- the analysis of Sec. 5.4 for priorities given by the caller ----
+def admissible_levels(batch, rng):
+    """Random GPU priority levels that agree with the CPU priority order on every core."""
+    N, n = batch["prio"].shape
+    levels = np.argsort(rng.random((N, n)), axis=1).astype(np.int32) + 1
+    for s in range(N):
+        for c in np.unique(batch["core"][s]):
+            on = np.flatnonzero(batch["core"][s] == c)
+            by_cpu = on[np.argsort(-batch["prio"][s, on], kind="stable")]  # highest CPU priority first
+            levels[s, by_cpu] = np.sort(levels[s, on])[::-1]
+    return levels
+
+
+def test_analysis_for_given_priorities(oracle, gpu):
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(12)
+    cases = [relaxed_workload(1_500, seed=6), few_gpu_tasks_workload(1_500, seed=6), taskgen.config(3, 1_000),
+             taskgen.config(4, 300), relaxed_workload(257, seed=3, n_cores=1, per_core=1, S=0)]
+    passing = 0
+    for batch in cases:
+        for wait in (BUSY, SUSPEND):
+            for gprio in (batch["prio"], admissible_levels(batch, rng)):
+                want_r, want_s = oracle.gprio_rta_batch(batch, gprio, wait)
+                got_r, got_s = B.gcaps_gprio_rta_batch(ctx, batch, wait, gprio)
+                assert np.array_equal(got_r, want_r), np.argwhere(got_r != want_r)[:5]
+                assert np.array_equal(got_s, want_s) and (got_r != -2).all()
+                passing += int(want_s.sum())
+    assert passing > 500
+    # what the search assigns passes here with the same bounds
+    batch = cases[0]
+    g, r, s = B.gcaps_gprio_assign_batch(ctx, batch, SUSPEND)
+    found = np.flatnonzero(s)
+    sub = {k: v[found] for k, v in batch.items()}
+    got_r, got_s = B.gcaps_gprio_rta_batch(ctx, sub, SUSPEND, g[found])
+    assert len(found) > 100 and (got_s == 1).all() and np.array_equal(got_r, r[found])
+
+
+def test_given_priorities_ties_big_values_and_rejections(oracle, gpu):
+    B, ctx, _ = gpu
+    rng = np.random.default_rng(13)
+    batch = relaxed_workload(1_200, seed=8, n_cores=2, per_core=4, S=2)
+    scale = rng.choice([1, 1, 300, 4000], size=(1200, 1)).astype(np.uint64)
+    for key in ("cpu_us", "period_us", "deadline_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale, 2**32 - 1).astype(np.uint32)
+    for key in ("gm_us", "ge_us"):
+        batch[key] = np.minimum(batch[key].astype(np.uint64) * scale[:, :, None], 2**32 - 1).astype(np.uint32)
+    batch["eps_us"] = rng.choice([0, 200, 70_000, 2**31], size=1200).astype(np.uint32)
+    tight = rng.random(batch["deadline_us"].shape) < 0.1  # own demand beyond the deadline: jitters at zero
+    batch["deadline_us"] = np.where(tight, np.maximum(1, batch["deadline_us"] // 50), batch["deadline_us"]).astype(np.uint32)
+    levels = admissible_levels(batch, rng)
+    coarse = (levels + 1) // 2 * np.int32(-2**30 // 4)  # ties and large negative values; order kept up to ties
+    for gprio in (levels, np.zeros_like(levels), -coarse):
+        try:
+            want = oracle.gprio_rta_batch(batch, gprio, BUSY)
+        except oracle.OracleError as e:
+            assert e.code == oracle.EORDER
+            with pytest.raises(B.GcapsError) as g:
+                B.gcaps_gprio_rta_batch(ctx, batch, BUSY, gprio)
+            assert g.value.code == B.GCAPS_ETASK and g.value.first_bad == e.first_bad
+            continue
+        got = B.gcaps_gprio_rta_batch(ctx, batch, BUSY, gprio)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    # an order that inverts two tasks of one core
+    bad = levels.copy()
+    s = 77
+    on = np.flatnonzero(batch["core"][s] == batch["core"][s, 0])
+    assert len(on) >= 2
+    a, b = on[0], on[1]
+    bad[s, a], bad[s, b] = bad[s, b], bad[s, a]
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_gprio_rta_batch(ctx, batch, SUSPEND, bad)
+    assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == s
+
+
+def test_given_priorities_device_entry_point_chunked(oracle, gpu, monkeypatch):
+    import torch
+    B, ctx, stream = gpu
+    batch = relaxed_workload(2_001, seed=14)
+    levels = admissible_levels(batch, np.random.default_rng(1))
+    want_r, want_s = oracle.gprio_rta_batch(batch, levels, SUSPEND)
+    d = B.to_device(batch)
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "640")
+    ctx2 = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        for c in (ctx, ctx2):
+            r = torch.full(want_r.shape, -7, dtype=torch.int64, device="cuda:0")
+            s = torch.full(want_s.shape, 9, dtype=torch.uint8, device="cuda:0")
+            torch.cuda.synchronize()
+            B.gcaps_gprio_rta_batch_device(c, d, SUSPEND, torch.from_numpy(levels).to("cuda:0"), r, s)
+            B.gcaps_status(c)
+            assert np.array_equal(r.cpu().numpy(), want_r) and np.array_equal(s.cpu().numpy(), want_s)
+    finally:
+        B.gcaps_destroy(ctx2)
