@@ -27,8 +27,8 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="73c92de895e021d14c70a2408ea787e51adfaab3c58ebe527376a32ad77456f8",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943834379, write_bytes=333289931)
+MEASURED_TRAFFIC = dict(csrc_sha256="c5969139a7d0c674fe1f79ff51b192455ab3cf82e6deac8f757ca7db6d32cd57",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943809077, write_bytes=333291600)
 
 
 def csrc_sha256():

@@ -128,6 +128,10 @@ int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wa
  * without waiting for it.  Argument errors are reported at once; task-model
  * violations are detected on the device and reported by gcaps_status().
  * Outputs of an invalid taskset are undefined, all others are complete.
+ * The launches of a call may be recorded into a HIP graph (stream capture) once a direct call with
+ * the same sizes has been made on the context: that call makes the device allocations, a recorded
+ * one makes none.  A recorded call depends on no earlier call and can be replayed any number of
+ * times, with direct calls in between.
  */
 int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
                            int64_t *d_out_resp, uint8_t *d_out_sched);

@@ -70,7 +70,13 @@ struct gcaps_ctx {
   bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
   u32 last_n_tasksets = 0;
   int lds_limit = 65536;     /* dynamic LDS a workgroup may ask for */
-  DeviceBuffer status;       /* u32 first_bad, u32 wide_count */
+  DeviceBuffer status;       /* three blocks of fast::kStatusWords words: two used by alternate calls, the
+                                third by calls recorded into a HIP graph */
+  u32 status_parity = 0;     /* block of the most recent call that ran directly */
+  u32 status_block = 0;      /* block of the current (most recent) call */
+  bool next_prepared = false; /* the other block has been made ready by the last kernel of that call */
+  u32 *next_status = nullptr; /* what the last kernel of the current chunk is to prepare, or null */
+  bool capturing = false;     /* the stream is recording the current call into a HIP graph */
   DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
   DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
   DeviceBuffer deep_sorted;  /* the same list, contiguous and ordered (binning) */
@@ -83,6 +89,10 @@ struct gcaps_ctx {
 };
 
 namespace {
+
+u32 *status_of(const gcaps_ctx *ctx) {
+  return (u32 *)ctx->status.ptr + (size_t)ctx->status_block * fast::kStatusWords;
+}
 
 struct DeviceGuard {
   int prev = -1;
@@ -141,13 +151,15 @@ int launch_wide(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode,
   int rc = wide_columns(ctx, b->n_tasks, slots, &ws);
   if (rc != GCAPS_OK) return rc;
   hipLaunchKernelGGL(wide::rta_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, policy,
-                     wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, ws, d_list, d_list_count,
-                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset, ctx->cont != 0);
+                     wait_mode, (long long *)d_resp, d_sched, status_of(ctx), ws, d_list, d_list_count,
+                     ctx->resp_stride, ctx->sched_stride, ctx->ts_offset, ctx->cont != 0, ctx->next_status,
+                     (u32)fast::kStatusWords);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
 /* Clears the per-call device words with a kernel (not a memset node) so that a caller
- * may capture the launches of one call into a HIP graph. */
+ * may capture the launches of one call into a HIP graph.  Outside a capture the first chunk of
+ * a call does not need it (see begin_chunk). */
 __global__ void reset_status_kernel(u32 *status, int first_chunk) {
   if (threadIdx.x == 0) {
     if (first_chunk) {
@@ -164,10 +176,21 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
   status[fast::ST_CLAIM + threadIdx.x] = 0; /* tiles handed out by the persistent launch (kClaimCounters = 64 words) */
 }
 
+/* Status words at the start of a chunk.  The first chunk of a call finds its block prepared by the
+ * last kernel of the previous call (see wide::prepare_next_call); otherwise a small kernel does it. */
+int begin_chunk(gcaps_ctx *ctx, bool first_chunk) {
+  if (first_chunk && ctx->next_prepared && !ctx->capturing) {
+    ctx->next_prepared = false;
+    return GCAPS_OK;
+  }
+  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, status_of(ctx), first_chunk ? 1 : 0);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
 /* the list between the two fast launches: regions filled by the first launch, or (binning) the
  * contiguous list ordered by bucket */
 fast::ListSpec deep_list_spec(const gcaps_ctx *ctx, bool sorted) {
-  u32 *status = (u32 *)ctx->status.ptr;
+  u32 *status = status_of(ctx);
   if (sorted)
     return fast::ListSpec{(u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u, nullptr, nullptr, nullptr};
   fast::ListSpec dl{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap,
@@ -186,7 +209,7 @@ int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mo
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, TS, false);
   fast::ListSpec dl = deep_list_spec(ctx, false);
   hipLaunchKernelGGL((fast::rta_fast_kernel<TS, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
-                     policy, wait_mode, (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr,
+                     policy, wait_mode, (long long *)d_resp, d_sched, status_of(ctx),
                      (u32 *)ctx->wide_list.ptr, dl, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
@@ -196,11 +219,11 @@ int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
   if (wait_mode == GCAPS_WAIT_BUSY)
     hipLaunchKernelGGL(fast::rta_screen_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr,
                        deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   else
     hipLaunchKernelGGL(fast::rta_screen_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr,
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr,
                        deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
@@ -242,7 +265,7 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
   fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0 && !CONT);
   if (CONT) dl = fast::ListSpec{nullptr, nullptr, 1u, N, nullptr, nullptr, nullptr}; /* every taskset */
   hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q, CONT>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                     (long long *)d_resp, d_sched, (u32 *)ctx->status.ptr, (u32 *)ctx->wide_list.ptr, dl, kr,
+                     (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr, dl, kr,
                      ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
@@ -275,9 +298,7 @@ int tile_width(const gcaps_ctx *ctx, u32 n, u32 kr) {
 /* one chunk: every array of it stays below 4 GiB, so the kernels index with 32 bits */
 int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
               uint8_t *d_sched, bool first_chunk) {
-  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr,
-                     first_chunk ? 1 : 0);
-  if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+  if (begin_chunk(ctx, first_chunk) != GCAPS_OK) return GCAPS_EDEVICE;
   const u32 n = b->n_tasks, N = b->n_tasksets;
   const u32 kr = n > ctx->screen_tasks ? ctx->screen_tasks : n;
   const int ts_screen = n <= fast::kMaxTasks ? tile_width(ctx, n, kr) : 0;
@@ -298,7 +319,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     /* continue-after-miss: nothing is settled early, the full-depth launch takes every taskset */
     rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched, 0u);
     if (rc != GCAPS_OK) return rc;
-    const u32 *count = (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT;
+    const u32 *count = (const u32 *)status_of(ctx) + fast::ST_WIDE_COUNT;
     return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count,
                        N < 65536u ? N : 65536u);
   }
@@ -315,7 +336,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     /* the list ordered by the bucket that the first launch gave every entry */
     rc = ctx->deep_sorted.reserve((size_t)N * sizeof(u32));
     if (rc != GCAPS_OK) return rc;
-    u32 *status = (u32 *)ctx->status.ptr;
+    u32 *status = status_of(ctx);
     hipLaunchKernelGGL(bin::order_kernel, dim3(fast::kListRegions), dim3(256), 0, ctx->stream,
                        deep_list_spec(ctx, false), (const u32 *)(status + fast::ST_ORDER_HIST),
                        (u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL);
@@ -326,7 +347,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     if (rc != GCAPS_OK) return rc;
   }
   /* whatever the fast launches handed over is redone in 64 bit; usually nothing */
-  const u32 *count = (const u32 *)ctx->status.ptr + fast::ST_WIDE_COUNT;
+  const u32 *count = (const u32 *)status_of(ctx) + fast::ST_WIDE_COUNT;
   const u32 items = N < 65536u ? N : 65536u;
   return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count, items);
 }
@@ -344,7 +365,29 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
   if (chunk > 64) chunk &= ~63ull;
   if (chunk < 1) chunk = 1;
   ctx->last_n_tasksets = b->n_tasksets;
+  /* This call takes the status block the previous call did not use; the last kernel of its last
+   * chunk prepares the other one for the call after it.  Launches that the stream is recording
+   * into a HIP graph must depend on nothing that ran before the graph and leave nothing behind
+   * that a later call relies on (a replay happens without this code knowing): such a call uses a
+   * block of its own, always starts with the reset kernel and prepares nothing. */
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(ctx->stream, &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    capture = hipStreamCaptureStatusNone;
+  }
+  ctx->capturing = capture != hipStreamCaptureStatusNone;
+  if (ctx->capturing) {
+    ctx->status_block = 2u;
+  } else {
+    ctx->status_parity ^= 1u;
+    ctx->status_block = ctx->status_parity;
+  }
+  bool prepared = false;
   for (u64 c0 = 0; c0 < N; c0 += chunk) {
+    const bool last_chunk = c0 + chunk >= N;
+    ctx->next_status = (last_chunk && !ctx->capturing)
+                           ? (u32 *)ctx->status.ptr + (size_t)(ctx->status_parity ^ 1u) * fast::kStatusWords
+                           : nullptr;
     gcaps_batch sub = *b;
     const u64 cn = N - c0 < chunk ? N - c0 : chunk;
     sub.n_tasksets = (u32)cn;
@@ -362,8 +405,14 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
     if (sub.ge_us) sub.ge_us += c0 * n * b->max_gseg;
     ctx->ts_offset = (u32)c0;
     const int rc = run(&sub, c0);
-    if (rc != GCAPS_OK) return rc;
+    ctx->next_status = nullptr;
+    if (rc != GCAPS_OK) {
+      if (!ctx->capturing) ctx->next_prepared = false; /* the next call resets its block itself */
+      return rc;
+    }
+    prepared = last_chunk;
   }
+  if (!ctx->capturing) ctx->next_prepared = prepared; /* a recorded call changes nothing for the others */
   return GCAPS_OK;
 }
 
@@ -380,11 +429,9 @@ int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, 
 /* GPU-segment priority assignment of one chunk */
 int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const uint8_t *d_skip, int32_t *d_gprio,
                     int64_t *d_resp, uint8_t *d_sched, bool first_chunk) {
-  hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr,
-                     first_chunk ? 1 : 0);
-  if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+  if (begin_chunk(ctx, first_chunk) != GCAPS_OK) return GCAPS_EDEVICE;
   const u32 N = b->n_tasksets, n = b->n_tasks;
-  u32 *status = (u32 *)ctx->status.ptr;
+  u32 *status = status_of(ctx);
   /* the quad-lane kernel takes shapes up to 32 tasks; what it cannot represent in 24 bits it lists */
   ctx->wide_only = n > 32 || gprio::gprio_lds_bytes(n) > (size_t)ctx->lds_limit;
   const u32 *d_list = nullptr, *d_count = nullptr;
@@ -439,7 +486,8 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
   int rc = wide_columns(ctx, n, slots, &ws);
   if (rc != GCAPS_OK) return rc;
   hipLaunchKernelGGL(gprio::gprio_wide_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *b, wait_mode, d_skip,
-                     (int *)d_gprio, (long long *)d_resp, d_sched, status, ws, d_list, d_count, ctx->ts_offset);
+                     (int *)d_gprio, (long long *)d_resp, d_sched, status, ws, d_list, d_count, ctx->ts_offset,
+                     ctx->next_status, (u32)fast::kStatusWords);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -457,8 +505,7 @@ int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const i
                     uint8_t *d_sched) {
   const u64 n = b->n_tasks;
   return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
-    hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, ctx->stream, (u32 *)ctx->status.ptr, c0 == 0 ? 1 : 0);
-    if (hipGetLastError() != hipSuccess) return (int)GCAPS_EDEVICE;
+    if (begin_chunk(ctx, c0 == 0) != GCAPS_OK) return (int)GCAPS_EDEVICE;
     ctx->wide_only = true;
     const u32 slots = wide_slots(ctx, sub->n_tasksets);
     wide::Scratch ws;
@@ -466,7 +513,7 @@ int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const i
     if (rc != GCAPS_OK) return rc;
     hipLaunchKernelGGL(gprio::gprio_given_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *sub, wait_mode,
                        (const int *)(d_gprio + c0 * n), (long long *)(d_resp + c0 * n), d_sched + c0,
-                       (u32 *)ctx->status.ptr, ws, ctx->ts_offset);
+                       status_of(ctx), ws, ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
     return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
   });
 }
@@ -557,7 +604,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (rc == GCAPS_OK && hipGetDeviceProperties(&prop, device_id) != hipSuccess) rc = GCAPS_EDEVICE;
   if (rc == GCAPS_OK) {
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    rc = ctx->status.reserve(fast::kStatusWords * sizeof(u32));
+    rc = ctx->status.reserve(3 * fast::kStatusWords * sizeof(u32));
   }
   if (rc == GCAPS_OK) {
     /* the fast kernel's tiles live in dynamic LDS: raise the per-workgroup limit to what the CU has */
@@ -635,7 +682,7 @@ extern "C" int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset) {
   if (!ctx) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, ctx->status.ptr, sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
           hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
@@ -652,7 +699,7 @@ extern "C" int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count) {
   if (!ctx || !count) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, ctx->status.ptr, 4 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), 4 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
           hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();

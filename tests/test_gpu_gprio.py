@@ -310,3 +310,44 @@ def test_given_priorities_device_entry_point_chunked(oracle, gpu, monkeypatch):
             assert np.array_equal(r.cpu().numpy(), want_r) and np.array_equal(s.cpu().numpy(), want_s)
     finally:
         B.gcaps_destroy(ctx2)
+
+
+def test_calls_of_every_kind_interleaved_on_one_context(oracle, gpu, monkeypatch):
+    """The per-call device words (invalid-taskset index, hand-over counts, list and tile counters) are
+    prepared for the next call by the last kernel of the one before it, whatever kind either is, also
+    after a call that reported an invalid taskset and with calls split into chunks."""
+    import torch
+    B, _, stream = gpu
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "448")
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        small = relaxed_workload(300, seed=41)          # one chunk
+        large = relaxed_workload(1_500, seed=42)        # four chunks
+        wide = relaxed_workload(400, seed=43, n_cores=2, per_core=4, S=2)
+        wide["period_us"] = (wide["period_us"].astype(np.uint64) * 3000).astype(np.uint32)  # beyond 24 bits
+        wide["deadline_us"] = wide["period_us"].copy()
+        bad = {k: v.copy() for k, v in small.items()}
+        bad["period_us"][123, 1] = 0
+        want = {}
+        for name, b in (("small", small), ("large", large), ("wide", wide)):
+            want[name] = (oracle.rta_batch(b, 3, SUSPEND, threads=16)[:2],
+                          oracle.gprio_assign_batch(b, SUSPEND, threads=16)[:3],
+                          oracle.gprio_rta_batch(b, b["prio"], SUSPEND))
+        batches = dict(small=small, large=large, wide=wide)
+        for round_ in range(2):
+            for name in ("small", "wide", "large", "small"):
+                b = batches[name]
+                got = B.gcaps_rta_batch(ctx, b, 3, SUSPEND)
+                assert all(np.array_equal(x, y) for x, y in zip(got, want[name][0])), (round_, name, "rta")
+                assert (B.gcaps_last_wide_count(ctx) > 0) == (name == "wide")
+                with pytest.raises(B.GcapsError) as e:
+                    B.gcaps_gprio_assign_batch(ctx, bad, SUSPEND)
+                assert e.value.first_bad == 123
+                got = B.gcaps_gprio_assign_batch(ctx, b, SUSPEND)
+                assert all(np.array_equal(x, y) for x, y in zip(got, want[name][1])), (round_, name, "assign")
+                got = B.gcaps_gprio_rta_batch(ctx, b, SUSPEND, b["prio"])
+                assert all(np.array_equal(x, y) for x, y in zip(got, want[name][2])), (round_, name, "given")
+                with pytest.raises(B.GcapsError):
+                    B.gcaps_rta_batch(ctx, bad, 3, SUSPEND)
+    finally:
+        B.gcaps_destroy(ctx)

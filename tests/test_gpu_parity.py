@@ -389,3 +389,40 @@ def test_continue_after_miss_reports_invalid_tasksets(gpu):
             assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 137
     finally:
         B.gcaps_destroy(ctx)
+
+
+def test_captured_call_replays(oracle, gpu):
+    """One device-entry call recorded into a HIP graph (after a warm-up call that made the context's
+    allocations) and replayed, with eager calls of other sizes in between: every replay gives the eager result."""
+    import torch
+    B, _, _ = gpu
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        batch, other = relaxed_workload(3_000, seed=51), relaxed_workload(777, seed=52)
+        want_r, want_s, _ = oracle.rta_batch(batch, BOTH, SUSPEND, threads=16)
+        d = B.to_device(batch)
+        N, n = batch["cpu_us"].shape
+        d_resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+        d_sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+        B.gcaps_rta_batch_device(ctx, d, BOTH, SUSPEND, d_resp, d_sched)  # warm-up: allocations happen here
+        B.gcaps_status(ctx)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.gcaps_rta_batch_device(ctx, d, BOTH, SUSPEND, d_resp, d_sched)
+        for k in range(4):
+            d_resp.fill_(-7)
+            d_sched.fill_(9)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(d_resp.cpu().numpy(), want_r) and np.array_equal(d_sched.cpu().numpy(), want_s), k
+            # eager work of the same context between the replays
+            got = B.gcaps_rta_batch(ctx, other, BOTH, BUSY)
+            ref = oracle.rta_batch(other, BOTH, BUSY, threads=16)
+            assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+            if k % 2:
+                B.gcaps_gprio_assign_batch(ctx, other, BUSY)
+        B.gcaps_status(ctx)
+    finally:
+        B.gcaps_destroy(ctx)
