@@ -31,6 +31,12 @@ MEASURED_TRAFFIC = dict(csrc_sha256="c5969139a7d0c674fe1f79ff51b192455ab3cf82e6d
                         workload=3, tasksets=1_000_000, fetch_bytes=943809077, write_bytes=333291600)
 
 
+# The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
+# profiles/gprio_step_workload3_hbm_traffic.md).
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="c5969139a7d0c674fe1f79ff51b192455ab3cf82e6deac8f757ca7db6d32cd57",
+                              workload=3, tasksets=1_000_000, fetch_bytes=1235194123, write_bytes=251366069)
+
+
 def csrc_sha256():
     import hashlib
     h = hashlib.sha256()
@@ -40,6 +46,17 @@ def csrc_sha256():
             h.update(name.encode())
             h.update(open(os.path.join(d, name), "rb").read())
     return h.hexdigest()
+
+
+def copy_calibration():
+    """Device-to-device copies of 1 GiB: a kernel of known traffic for scaling the HBM byte counters."""
+    import torch
+    src = torch.zeros(2**28, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def algorithmic_bytes_per_taskset(n, S, npol):
@@ -136,12 +153,7 @@ def main():
                            sched_ratio_rr=float(d_sched[1].float().mean().item()),
                            tasksets_via_64bit_kernel=B.gcaps_last_wide_count(ctx))
     if args.copy_calibration:
-        src = torch.zeros(2**28, dtype=torch.int32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration()
     head = min(modes, key=lambda m: modes[m]["tasksets_per_s"])
     head_wait = B.GCAPS_WAIT_BUSY if head == "busy" else B.GCAPS_WAIT_SUSPEND
 
@@ -274,6 +286,8 @@ def bench_gprio(args, batch, N, cores, per_core, S):
                    sample=f"first {sample} tasksets of the workload (same skip flags), {head} mode, "
                           f"{threads} std::thread workers over tasksets",
                    gpu_matches_oracle_on_sample=same)
+    if args.copy_calibration:
+        copy_calibration()
     for mm in modes.values():
         mm.pop("skip")
     m = modes[head]
@@ -281,8 +295,13 @@ def bench_gprio(args, batch, N, cores, per_core, S):
     per_output = n * (4 + 8) + 1                         # level, bound; verdict
     alg_bytes = m["searched"] * per_searched + (N - m["searched"]) * 1 + N * per_output
     achieved = alg_bytes / (m["device_ms_per_step"] * 1e-3) / 1e9
+    traffic = None
+    mt = MEASURED_TRAFFIC_GPRIO
+    if (mt["csrc_sha256"] and args.workload == mt["workload"] and N == mt["tasksets"] and not args.search_all
+            and mt["csrc_sha256"] == csrc_sha256()):
+        traffic = mt["fetch_bytes"] + mt["write_bytes"]
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="gcaps_gprio_assign_batch_device (all launches of one step)",
+                    traffic=traffic, kernel="gcaps_gprio_assign_batch_device (all launches of one step)",
                     algorithmic_bytes_per_step=alg_bytes)
     out = dict(metric="tasksets through the GPU-segment priority search/sec, 1 MI355X", value=m["tasksets_per_s"],
                unit="tasksets/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=m["wall_ms_per_step"],
