@@ -27,14 +27,14 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="c5969139a7d0c674fe1f79ff51b192455ab3cf82e6deac8f757ca7db6d32cd57",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943809077, write_bytes=333291600)
+MEASURED_TRAFFIC = dict(csrc_sha256="3b05ab6c9a2b9b13882293b848c4d2ec09b5c053ab761ca9ea04d3f6674c5973",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943823520, write_bytes=333291989)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="c5969139a7d0c674fe1f79ff51b192455ab3cf82e6deac8f757ca7db6d32cd57",
-                              workload=3, tasksets=1_000_000, fetch_bytes=1235194123, write_bytes=251366069)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="3b05ab6c9a2b9b13882293b848c4d2ec09b5c053ab761ca9ea04d3f6674c5973",
+                              workload=3, tasksets=1_000_000, fetch_bytes=1235805227, write_bytes=251417080)
 
 
 def csrc_sha256():
