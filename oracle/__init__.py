@@ -1,8 +1,9 @@
 """ctypes access to the CPU oracle (test infrastructure only).
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg import this
-package.  It marshals numpy arrays into ``liboracle_rta.so`` (built from
-``rta_oracle.cpp`` with g++) and holds no arithmetic of its own.
+package.  It marshals numpy arrays into ``liboracle_rta.so`` (the analysis, built from
+``rta_oracle.cpp`` with g++) and ``liboracle_sim.so`` (the unit-tick simulator, built from
+``sim_oracle.cpp``) and holds no arithmetic of its own.
 """
 import ctypes
 import os
@@ -12,7 +13,9 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_DIR, "liboracle_rta.so")
+_SIM_PATH = os.path.join(_DIR, "liboracle_sim.so")
 _lib = None
+_sim = None
 
 POLICY_GCAPS = 1
 POLICY_RR = 2
@@ -39,7 +42,32 @@ def build(force=False):
     cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
            "-o", _LIB_PATH, src]
     subprocess.run(cmd, check=True, cwd=_DIR)
+    build_sim(force)
     return _LIB_PATH
+
+
+def build_sim(force=False):
+    """Compile sim_oracle.cpp into liboracle_sim.so (g++, host only)."""
+    src = os.path.join(_DIR, "sim_oracle.cpp")
+    if force or not os.path.exists(_SIM_PATH) or os.path.getmtime(_SIM_PATH) < os.path.getmtime(src):
+        subprocess.run(["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
+                        "-o", _SIM_PATH, src], check=True, cwd=_DIR)
+    return _SIM_PATH
+
+
+def sim_library():
+    """The simulator's library (ctypes), built on first use."""
+    global _sim
+    if _sim is None:
+        build_sim()
+        _sim = ctypes.CDLL(_SIM_PATH)
+        _sim.des_run.restype = ctypes.c_int
+        _sim.des_run_gprio.restype = ctypes.c_int
+        u32, i32, p = ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
+        _sim.oracle_simulate_batch.restype = ctypes.c_int
+        _sim.oracle_simulate_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, p, i32, i32, u32, i32,
+                                               p, p, p, p]
+    return _sim
 
 
 def _open(path):
@@ -265,3 +293,37 @@ def gprio_rta_batch(batch, gprio, wait_mode, *, options=0, lib=None):
     if rc != OK:
         raise OracleError(rc, int(bad[0]))
     return resp, sched
+
+
+def simulate_batch(batch, policy_mask, wait_mode, horizon, offset=None, threads=None):
+    """Unit-tick simulation of every taskset of a batch (dict of numpy arrays, analysis layout).
+    Returns (mort[P,N,n] int64, jobs[P,N,n] uint32, flag[P,N] uint8); raises ValueError with the index of
+    the first taskset that breaks the task model."""
+    C = np.ascontiguousarray(batch["cpu_us"], dtype=np.uint32)
+    N, n = C.shape
+    gm = np.ascontiguousarray(batch["gm_us"], dtype=np.uint32)
+    ge = np.ascontiguousarray(batch["ge_us"], dtype=np.uint32)
+    S = gm.shape[2]
+    P = 2 if policy_mask == POLICY_BOTH else 1
+    arrs = [np.ascontiguousarray(batch[k], dtype=t) for k, t in
+            (("theta_us", np.uint32), ("eps_us", np.uint32), ("slice_us", np.uint32))]
+    T = np.ascontiguousarray(batch["period_us"], dtype=np.uint32)
+    prio = np.ascontiguousarray(batch["prio"], dtype=np.int32)
+    core = np.ascontiguousarray(batch["core"], dtype=np.uint8)
+    eta = np.ascontiguousarray(batch["n_gseg"], dtype=np.uint8)
+    off = None if offset is None else np.ascontiguousarray(offset, dtype=np.uint32)
+    assert off is None or off.shape == (N, n)
+    mort = np.empty((P, N, n), np.int64)
+    jobs = np.empty((P, N, n), np.uint32)
+    flag = np.empty((P, N), np.uint8)
+    bad = ctypes.c_int64(-1)
+    ptr = lambda a: None if a is None or a.size == 0 else a.ctypes.data_as(ctypes.c_void_p)
+    if threads is None:
+        threads = min(16, os.cpu_count() or 1)
+    rc = sim_library().oracle_simulate_batch(N, n, S, ptr(arrs[0]), ptr(arrs[1]), ptr(arrs[2]), ptr(C), ptr(T),
+                                             ptr(prio), ptr(core), ptr(eta), ptr(gm), ptr(ge), ptr(off),
+                                             policy_mask, wait_mode, int(horizon), threads, ptr(mort), ptr(jobs),
+                                             ptr(flag), ctypes.byref(bad))
+    if rc != 0:
+        raise ValueError(f"simulate_batch: rc={rc}, first bad taskset {bad.value}")
+    return mort, jobs, flag

@@ -1,9 +1,11 @@
 /*
- * Discrete-event (unit-tick) simulator of a tiny multi-core + one-GPU system.
- * TEST TOOL ONLY: it is one of the pins of the CPU oracle and shares no code
- * with the oracle or with the GPU library.  It executes a concrete schedule and
- * reports the largest response time each task was seen to have; the analytic
- * bounds of Sec. 5 must never be below that.
+ * Simulation oracle: unit-tick simulator of a multi-core + one-GPU system.
+ * TEST INFRASTRUCTURE ONLY.  It is the reference the batched simulator of the GPU
+ * library is compared with, and one of the pins of the analysis oracle
+ * (rta_oracle.cpp); it shares no code with either.  It executes a concrete
+ * schedule one tick at a time and reports the largest response time each task
+ * was seen to have (Sec. 6.2 calls it the maximum observed response time); the
+ * analytic bounds of Sec. 5 must never be below that.
  *
  * Model (Sec. 2, Sec. 3, Sec. 4.1-4.2, Alg. 1):
  *  - CPU: partitioned, fixed-priority, fully preemptive, one task per core per tick.
@@ -25,44 +27,56 @@
  *    highest-priority requester that is able to run on its core.  A task waiting for
  *    the lock behaves like a task waiting for the GPU (spins or sleeps).
  *  - Only the task at the head of the running set makes GPU progress.
+ *  - Whatever happens at the same instant happens in decreasing CPU priority (equal priorities:
+ *    lower caller index first), so a result does not depend on the order the caller lists the tasks in.
+ *    Internally the tasks are held in that order; `caller` maps back.
+ *
+ * Parity: pinned by tests/test_oracle_des.py and tests/test_oracle_sim.py (hand-worked schedules, the
+ * motivational example of Sec. 4, closed forms of single-core fixed-priority scheduling, the bounds of
+ * Sec. 5 from above, invariance under task permutation).
  */
 #include <stdint.h>
 
 #include <algorithm>
 #include <deque>
+#include <numeric>
+#include <thread>
 #include <vector>
 
 namespace {
 
 enum Phase { PH_CPU, PH_UPD_BEGIN, PH_GPU, PH_UPD_END };
 
+typedef int64_t tick_t;
+
 struct Op {
   Phase ph;
-  int len;
+  tick_t len;
 };
 
 struct TaskDef {
-  int core, prio, gprio, T, D, offset, eta; /* gprio: priority of the GPU segments (Sec. 4.3) */
-  std::vector<int> c;      /* eta + 1 CPU segments */
-  std::vector<int> gm, ge; /* eta GPU segments */
+  int core, prio, gprio, eta, caller; /* gprio: priority of the GPU segments (Sec. 4.3) */
+  tick_t T, offset;
+  std::vector<tick_t> c;      /* eta + 1 CPU segments */
+  std::vector<tick_t> gm, ge; /* eta GPU segments */
 };
 
 struct TaskState {
   std::vector<Op> ops; /* program of one job */
   bool active = false;
   size_t pc = 0;
-  int remaining = 0;
+  tick_t remaining = 0;
   bool in_update = false; /* holds the driver lock, non-preemptible */
-  int release = 0;
-  int max_resp = 0;
-  int jobs_done = 0;
+  tick_t release = 0;
+  tick_t max_resp = 0;
+  int64_t jobs_done = 0;
 };
 
 struct Sim {
   int n;
   int policy; /* 1 = GCAPS, 2 = round-robin */
   int wait;   /* 0 = busy, 1 = suspend */
-  int theta, eps, L;
+  tick_t theta, eps, L;
   std::vector<TaskDef> def;
   std::vector<TaskState> st;
   int n_cores = 0;
@@ -74,8 +88,8 @@ struct Sim {
 
   /* round-robin ring */
   std::deque<int> ring; /* head = TSG on the GPU */
-  int slice_used = 0;
-  int switch_left = 0;
+  tick_t slice_used = 0;
+  tick_t switch_left = 0;
 
   bool overrun = false;
 
@@ -130,7 +144,7 @@ struct Sim {
     if (s.ops[s.pc].ph == PH_GPU && policy == 2 && s.remaining > 0) ring.push_back(i);
   }
 
-  void finish_job(int i, int now_end) {
+  void finish_job(int i, tick_t now_end) {
     TaskState &s = st[i];
     s.active = false;
     s.max_resp = std::max(s.max_resp, now_end - s.release);
@@ -138,7 +152,7 @@ struct Sim {
   }
 
   /* Advance over everything that takes no time.  `t` is the start of the current tick. */
-  void settle(int t) {
+  void settle(tick_t t) {
     bool moved = true;
     while (moved) {
       moved = false;
@@ -192,7 +206,7 @@ struct Sim {
     return ph == PH_UPD_BEGIN || ph == PH_UPD_END;
   }
 
-  void tick(int t) {
+  void tick(tick_t t) {
     /* releases */
     for (int i = 0; i < n; ++i) {
       if (t >= def[i].offset && (t - def[i].offset) % def[i].T == 0) {
@@ -226,10 +240,8 @@ struct Sim {
     /* driver lock: highest-priority requester that is at the top of its core */
     if (policy == 1 && lock_holder < 0) {
       int g = -1;
-      for (int c = 0; c < n_cores; ++c) {
-        int i = on_core[c];
-        if (i >= 0 && is_update_waiter(i) && (g < 0 || higher(i, g))) g = i;
-      }
+      for (int i = 0; i < n; ++i)
+        if (on_core[def[i].core] == i && is_update_waiter(i) && (g < 0 || higher(i, g))) g = i;
       if (g >= 0) {
         lock_holder = g;
         st[g].in_update = true;
@@ -304,6 +316,37 @@ struct Sim {
   }
 };
 
+/* Runs one schedule over tasks given in caller order; results come back in caller order. */
+int run_schedule(std::vector<TaskDef> tasks, int policy, int wait, tick_t theta, tick_t eps, tick_t L,
+                 tick_t horizon, tick_t *max_resp, int64_t *jobs_done) {
+  const int n = (int)tasks.size();
+  for (int i = 0; i < n; ++i) tasks[i].caller = i;
+  std::stable_sort(tasks.begin(), tasks.end(), [](const TaskDef &a, const TaskDef &b) { return a.prio > b.prio; });
+  Sim sim;
+  sim.n = n;
+  sim.policy = policy;
+  sim.wait = wait;
+  sim.theta = theta;
+  sim.eps = eps;
+  sim.L = L;
+  sim.def = tasks;
+  sim.st.resize(n);
+  sim.pending.assign(n, 0);
+  for (int i = 0; i < n; ++i) {
+    sim.n_cores = std::max(sim.n_cores, sim.def[i].core + 1);
+    sim.build_program(i);
+  }
+  for (tick_t t = 0; t < horizon; ++t) {
+    sim.tick(t);
+    if (sim.overrun) break;
+  }
+  for (int i = 0; i < n; ++i) {
+    max_resp[sim.def[i].caller] = sim.st[i].max_resp;
+    jobs_done[sim.def[i].caller] = sim.st[i].jobs_done;
+  }
+  return sim.overrun ? 1 : 0;
+}
+
 }  // namespace
 
 /*
@@ -320,46 +363,34 @@ extern "C" int des_run_gprio(int n, int max_eta, int policy, int wait_mode, int 
                              const int *core, const int *prio, const int *gprio, const int *T, const int *D,
                              const int *offset, const int *eta, const int *c, const int *gm,
                              const int *ge, int horizon, int *max_resp, int *jobs_done) {
-  if (n <= 0 || n > 16 || max_eta < 0 || L <= 0 || (policy != 1 && policy != 2) ||
+  (void)D;
+  if (n <= 0 || n > 255 || max_eta < 0 || L <= 0 || (policy != 1 && policy != 2) ||
       (wait_mode != 0 && wait_mode != 1))
     return -1;
-  Sim sim;
-  sim.n = n;
-  sim.policy = policy;
-  sim.wait = wait_mode;
-  sim.theta = theta;
-  sim.eps = eps;
-  sim.L = L;
-  sim.def.resize(n);
-  sim.st.resize(n);
-  sim.pending.assign(n, 0);
+  std::vector<TaskDef> tasks(n);
   for (int i = 0; i < n; ++i) {
-    TaskDef &d = sim.def[i];
+    TaskDef &d = tasks[i];
     d.core = core[i];
     d.prio = prio[i];
     d.gprio = gprio ? gprio[i] : prio[i];
     d.T = T[i];
-    d.D = D[i];
     d.offset = offset[i];
     d.eta = eta[i];
-    if (d.eta > max_eta || d.T <= 0 || d.core < 0 || d.core >= 64) return -1;
-    sim.n_cores = std::max(sim.n_cores, d.core + 1);
+    if (d.eta > max_eta || d.T <= 0 || d.core < 0 || d.core >= 256) return -1;
     for (int j = 0; j <= d.eta; ++j) d.c.push_back(c[i * (max_eta + 1) + j]);
     for (int j = 0; j < d.eta; ++j) {
       d.gm.push_back(gm[i * max_eta + j]);
       d.ge.push_back(ge[i * max_eta + j]);
     }
-    sim.build_program(i);
   }
-  for (int t = 0; t < horizon; ++t) {
-    sim.tick(t);
-    if (sim.overrun) break;
-  }
+  std::vector<tick_t> mr(n);
+  std::vector<int64_t> jd(n);
+  const int rc = run_schedule(tasks, policy, wait_mode, theta, eps, L, horizon, mr.data(), jd.data());
   for (int i = 0; i < n; ++i) {
-    max_resp[i] = sim.st[i].max_resp;
-    jobs_done[i] = sim.st[i].jobs_done;
+    max_resp[i] = (int)mr[i];
+    jobs_done[i] = (int)jd[i];
   }
-  return sim.overrun ? 1 : 0;
+  return rc;
 }
 
 extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
@@ -368,4 +399,79 @@ extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta,
                        const int *ge, int horizon, int *max_resp, int *jobs_done) {
   return des_run_gprio(n, max_eta, policy, wait_mode, theta, eps, L, core, prio, nullptr, T, D, offset, eta, c,
                        gm, ge, horizon, max_resp, jobs_done);
+}
+
+/*
+ * Simulates every taskset of a batch in the layout of the analysis (per-taskset theta, eps, L; per-task
+ * C, T, prio, core, eta^g; per-segment G^m, G^e; one time unit = one tick).  The task model of Sec. 3 gives a
+ * job eta^g + 1 CPU segments around its eta^g GPU segments but only their sum C_i; C_i is dealt to them as
+ * evenly as integers allow, the first C_i mod (eta^g + 1) segments one tick longer.  offset: [N][n] first
+ * release of each task, or null for a synchronous release at time 0.  policy_mask: 1 = GCAPS, 2 = round-robin,
+ * 3 = both (planes in that order).  Outputs per plane: out_mort [N][n] largest response time of the jobs that
+ * completed within `horizon` ticks (0 when none did), out_jobs [N][n] their number, out_flag [N] 1 when a job was
+ * released while its predecessor was still running (the simulation of that taskset stops there and the outputs
+ * hold what was seen until then), else 0.
+ * Returns 0; -1 on bad arguments; -2 when a taskset breaks the task model (T = 0, L = 0, eta^g > S), with
+ * *first_bad = its index (else -1).
+ */
+extern "C" int oracle_simulate_batch(uint32_t N, uint32_t n, uint32_t S, const uint32_t *theta,
+                                     const uint32_t *eps, const uint32_t *L, const uint32_t *C, const uint32_t *T,
+                                     const int32_t *prio, const uint8_t *core, const uint8_t *n_gseg,
+                                     const uint32_t *gm, const uint32_t *ge, const uint32_t *offset,
+                                     int policy_mask, int wait_mode, uint32_t horizon, int threads,
+                                     int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag, int64_t *first_bad) {
+  if (first_bad) *first_bad = -1;
+  if (N == 0 || n == 0 || n > 255 || S > 255 || !theta || !eps || !L || !C || !T || !prio || !core || !n_gseg ||
+      (S > 0 && (!gm || !ge)) || policy_mask < 1 || policy_mask > 3 || (wait_mode != 0 && wait_mode != 1) ||
+      !out_mort || !out_jobs || !out_flag)
+    return -1;
+  for (uint32_t ts = 0; ts < N; ++ts) {
+    bool bad = L[ts] == 0;
+    for (uint32_t i = 0; i < n; ++i) bad = bad || T[(size_t)ts * n + i] == 0 || n_gseg[(size_t)ts * n + i] > S;
+    if (bad) {
+      if (first_bad) *first_bad = ts;
+      return -2;
+    }
+  }
+  auto work = [&](uint32_t lo, uint32_t hi) {
+    std::vector<tick_t> mr(n);
+    std::vector<int64_t> jd(n);
+    for (uint32_t ts = lo; ts < hi; ++ts) {
+      std::vector<TaskDef> tasks(n);
+      for (uint32_t i = 0; i < n; ++i) {
+        const size_t at = (size_t)ts * n + i;
+        TaskDef &d = tasks[i];
+        d.core = core[at];
+        d.prio = prio[at];
+        d.gprio = prio[at];
+        d.T = T[at];
+        d.offset = offset ? offset[at] : 0;
+        d.eta = n_gseg[at];
+        const tick_t parts = d.eta + 1, each = C[at] / parts, longer = C[at] % parts;
+        for (int j = 0; j <= d.eta; ++j) d.c.push_back(each + (j < longer ? 1 : 0));
+        for (int j = 0; j < d.eta; ++j) {
+          d.gm.push_back(gm[at * S + j]);
+          d.ge.push_back(ge[at * S + j]);
+        }
+      }
+      int plane = 0;
+      for (int policy = 1; policy <= 2; ++policy) {
+        if (!(policy_mask & policy)) continue;
+        const int rc = run_schedule(tasks, policy, wait_mode, theta[ts], eps[ts], L[ts], horizon, mr.data(), jd.data());
+        const size_t base = ((size_t)plane * N + ts) * n;
+        for (uint32_t i = 0; i < n; ++i) {
+          out_mort[base + i] = mr[i];
+          out_jobs[base + i] = (uint32_t)jd[i];
+        }
+        out_flag[(size_t)plane * N + ts] = (uint8_t)rc;
+        ++plane;
+      }
+    }
+  };
+  const uint32_t workers = (uint32_t)std::max(1, std::min<int>(threads, (int)N));
+  std::vector<std::thread> pool;
+  for (uint32_t w = 0; w < workers; ++w)
+    pool.emplace_back(work, (uint32_t)((uint64_t)N * w / workers), (uint32_t)((uint64_t)N * (w + 1) / workers));
+  for (auto &th : pool) th.join();
+  return 0;
 }

@@ -1,31 +1,17 @@
-"""Builds and wraps the discrete-event simulator under tests/des/ (host only)."""
+"""Per-task wrapper of the unit-tick simulator (oracle/sim_oracle.cpp, host only)."""
 import ctypes
-import os
-import subprocess
 
 import numpy as np
 
-_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "des")
-_SRC = os.path.join(_DIR, "des_sim.cpp")
-_LIB = os.path.join(_DIR, "libdes_sim.so")
-_lib = None
+import oracle
 
 
 def build(force=False):
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.run(["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
-                        "-o", _LIB, _SRC], check=True)
-    return _LIB
+    return oracle.build_sim(force)
 
 
 def _load():
-    global _lib
-    if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
-        _lib.des_run.restype = ctypes.c_int
-        _lib.des_run_gprio.restype = ctypes.c_int
-    return _lib
+    return oracle.sim_library()
 
 
 def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon, gprio=None):

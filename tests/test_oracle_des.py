@@ -1,5 +1,5 @@
 """The analytic bounds must dominate every response time a concrete schedule produces.
-A unit-tick simulator (tests/des/des_sim.cpp, independent of the oracle) runs tiny tasksets
+A unit-tick simulator (oracle/sim_oracle.cpp, independent of the analysis oracle) runs tiny tasksets
 under both GPU policies and both waiting modes; for tasksets the oracle calls schedulable no
 job may respond later than its bound.
 
