@@ -211,6 +211,50 @@ int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int w
                                  int64_t *d_out_resp, uint8_t *d_out_sched);
 
 /*
+ * Schedule simulation (the observed response times that Sec. 6.2 and Table 5 set against the bounds of Sec. 5):
+ * every taskset of the batch is run as a concrete schedule from time 0 to `horizon` (one time unit = one
+ * unit of the batch's values) and the largest response time of each task is reported.
+ * The system that is simulated (Sec. 2, Sec. 3, Sec. 4.1-4.2, Alg. 1):
+ *   - partitioned, fully preemptive fixed-priority CPUs; prio as in the analysis (larger = higher; equal
+ *     values: lower caller index first);
+ *   - a job of tau_i is eta^g_i + 1 CPU segments around its eta^g_i GPU segments; C_i is dealt to the CPU
+ *     segments as evenly as integers allow, the first C_i mod (eta^g_i + 1) of them one unit longer; GPU segment
+ *     j is G^m_{i,j} of CPU work, then G^e_{i,j} of GPU work during which the task keeps its core
+ *     (GCAPS_WAIT_BUSY; it can be preempted there) or leaves it (GCAPS_WAIT_SUSPEND);
+ *   - GCAPS_POLICY_RR: the tasks with outstanding GPU work form a FIFO ring; the head runs for at most L, then,
+ *     if another waits, goes to the tail after a switch of theta; a switch also follows a completed segment
+ *     when another task waits;
+ *   - GCAPS_POLICY_GCAPS: the GPU work of a segment lies between two runlist updates decided as in Alg. 1; an
+ *     update that changes the running TSGs takes eps on the caller's core under the driver lock (not
+ *     preemptible; the lock goes to the highest-priority requester that holds its core; a requester without
+ *     the lock spins or, under self-suspension, steps aside), one that only joins or leaves the pending list
+ *     takes no time; only the task whose TSGs are running makes GPU progress;
+ *   - releases are strictly periodic: tau_i at offset_i, offset_i + T_i, ...; deadline_us is not used and
+ *     may be NULL;
+ *   - events of one instant take effect in decreasing priority, so results do not depend on caller order.
+ *   offset     uint32 [n_tasksets][n_tasks] first releases, or NULL: all released at 0
+ *   policy     GCAPS_POLICY_*; BOTH: two output planes, GCAPS then round-robin
+ *   horizon    1..2^31: length of the simulated interval
+ *   out_mort   int64 [P][n_tasksets][n_tasks]: largest response time among the jobs that completed
+ *              within the horizon, 0 when none did
+ *   out_jobs   uint32 [P][n_tasksets][n_tasks]: number of those jobs
+ *   out_flag   uint8 [P][n_tasksets]: 1 when a job was released while its predecessor was still running; the
+ *              simulation of that taskset stops there and its outputs hold what had completed until then
+ * Limits: n_tasks <= 32 (else GCAPS_EINVAL); a taskset with T = 0, L = 0, eta^g > S or a core index >= 64
+ * makes the call fail with GCAPS_ETASK (smallest index; outputs unspecified).
+ * One lane simulates one taskset under one policy and jumps from event to event (end of a segment, slice,
+ * switch or update; a release).  gcaps_simulate_batch takes HOST pointers and returns when the results are in
+ * place; gcaps_simulate_batch_device takes DEVICE pointers, queues the work on the context's stream and
+ * returns (errors as gcaps_rta_batch_device; gcaps_status reports on it likewise).
+ */
+int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, int policy,
+                         int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag,
+                         uint32_t *first_bad_taskset);
+int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset, int policy,
+                                int wait_mode, uint32_t horizon, int64_t *d_out_mort, uint32_t *d_out_jobs,
+                                uint8_t *d_out_flag);
+
+/*
  * Optional ordering (off by default) of the tasksets that need the second,
  * full-depth launch: a counting sort by how close to its deadline the last task
  * analysed in the first launch comes (R_k / D_k, 256 buckets, most slack first),

@@ -26,7 +26,7 @@ GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
-           "gcaps_gprio_rta_batch_device"]
+           "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -271,5 +271,60 @@ def gcaps_gprio_rta_batch_device(ctx, dbatch, wait_mode, d_gprio, d_resp, d_sche
         assert t.is_cuda and t.is_contiguous() and t.numel() == count and t.element_size() == size
     rc = _lib.gcaps_gprio_rta_batch_device(ctx, ctypes.byref(b), wait_mode, d_gprio.data_ptr(), d_resp.data_ptr(),
                                            d_sched.data_ptr())
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+
+
+_lib.gcaps_simulate_batch.restype = _int
+_lib.gcaps_simulate_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _int, _int, _u32, _p, _p, _p,
+                                      ctypes.POINTER(_u32)]
+_lib.gcaps_simulate_batch_device.restype = _int
+_lib.gcaps_simulate_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _int, _int, _u32, _p, _p, _p]
+
+
+def gcaps_simulate_batch(ctx, batch, policy, wait_mode, horizon, offset=None):
+    """Host entry point of the schedule simulation.  offset: uint32 [N, n] first releases or None.
+    Returns (mort int64 [P, N, n], jobs uint32 [P, N, n], flag uint8 [P, N])."""
+    N, n, S = _shape(batch)
+    keep = {}
+    b = gcaps_batch(n_tasksets=N, n_tasks=n, max_gseg=S)
+    for name, dtype, ndim in _FIELDS:
+        a = np.ascontiguousarray(batch[name], dtype=dtype)
+        assert a.ndim == ndim and a.shape[0] == N, name
+        keep[name] = a
+        setattr(b, name, a.ctypes.data if a.size else None)
+    off = None if offset is None else np.ascontiguousarray(offset, dtype=np.uint32)
+    assert off is None or off.shape == (N, n)
+    P = 2 if policy == GCAPS_POLICY_BOTH else 1
+    mort = np.empty((P, N, n), np.int64)
+    jobs = np.empty((P, N, n), np.uint32)
+    flag = np.empty((P, N), np.uint8)
+    bad = _u32(0xFFFFFFFF)
+    rc = _lib.gcaps_simulate_batch(ctx, ctypes.byref(b), None if off is None else off.ctypes.data, policy, wait_mode,
+                                   int(horizon), mort.ctypes.data, jobs.ctypes.data, flag.ctypes.data,
+                                   ctypes.byref(bad))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc, bad.value if rc == GCAPS_ETASK else None)
+    return mort, jobs, flag
+
+
+def gcaps_simulate_batch_device(ctx, dbatch, policy, wait_mode, horizon, d_mort, d_jobs, d_flag, d_offset=None):
+    """Device entry point of the schedule simulation (queued on the context's stream)."""
+    N, n = dbatch["cpu_us"].shape
+    S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
+    b = gcaps_batch(n_tasksets=int(N), n_tasks=int(n), max_gseg=int(S))
+    for name, _, _ in _FIELDS:
+        t = dbatch[name]
+        assert t.is_cuda and t.is_contiguous(), name
+        setattr(b, name, t.data_ptr() if t.numel() else None)
+    P = 2 if policy == GCAPS_POLICY_BOTH else 1
+    for t, count, size in ((d_mort, P * N * n, 8), (d_jobs, P * N * n, 4), (d_flag, P * N, 1)):
+        assert t.is_cuda and t.is_contiguous() and t.numel() == count and t.element_size() == size
+    if d_offset is not None:
+        assert d_offset.is_cuda and d_offset.is_contiguous() and d_offset.numel() == N * n
+        assert d_offset.element_size() == 4
+    rc = _lib.gcaps_simulate_batch_device(ctx, ctypes.byref(b), None if d_offset is None else d_offset.data_ptr(),
+                                          policy, wait_mode, int(horizon), d_mort.data_ptr(), d_jobs.data_ptr(),
+                                          d_flag.data_ptr())
     if rc != GCAPS_OK:
         raise GcapsError(rc)

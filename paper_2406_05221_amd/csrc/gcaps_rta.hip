@@ -20,6 +20,7 @@
 #include "rta_bin.hip.inc"
 #include "gprio_wide.hip.inc"
 #include "gprio_fast.hip.inc"
+#include "sim.hip.inc"
 
 namespace {
 
@@ -396,7 +397,7 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
     if (sub.slice_us) sub.slice_us += c0;
     sub.cpu_us += c0 * n;
     sub.period_us += c0 * n;
-    sub.deadline_us += c0 * n;
+    if (sub.deadline_us) sub.deadline_us += c0 * n;
     sub.prio += c0 * n;
     sub.core += c0 * n;
     sub.n_gseg += c0 * n;
@@ -516,6 +517,37 @@ int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const i
                        status_of(ctx), ws, ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
     return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
   });
+}
+
+/* Schedule simulation (Sec. 6.2: observed response times) of every taskset, one lane each */
+int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset, int policy, int wait_mode,
+                 uint32_t horizon, int64_t *d_mort, uint32_t *d_jobs, uint8_t *d_flag) {
+  const u64 n = b->n_tasks, N = b->n_tasksets;
+  const size_t lds = sim::lds_bytes(b->n_tasks);
+  if (lds > (size_t)ctx->lds_limit) return GCAPS_EINVAL;
+  const u32 planes = policy == GCAPS_POLICY_BOTH ? 2u : 1u;
+  return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
+    if (begin_chunk(ctx, c0 == 0) != GCAPS_OK) return (int)GCAPS_EDEVICE;
+    ctx->wide_only = true;
+    hipLaunchKernelGGL(sim::simulate_kernel, dim3((sub->n_tasksets + 63u) / 64u, planes), dim3(64), lds, ctx->stream,
+                       *sub, d_offset ? d_offset + c0 * n : nullptr, policy, wait_mode, horizon,
+                       (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
+                       status_of(ctx), ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
+    return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
+  });
+}
+
+int check_simulate(const gcaps_batch *b, int policy, int wait_mode, uint32_t horizon, const void *mort,
+                   const void *jobs, const void *flag) {
+  if (!b || !mort || !jobs || !flag) return GCAPS_EINVAL;
+  if (b->n_tasksets == 0 || b->n_tasks == 0 || b->n_tasks > sim::kMaxTasks || b->max_gseg > 255) return GCAPS_EINVAL;
+  if (!b->theta_us || !b->eps_us || !b->slice_us || !b->cpu_us || !b->period_us || !b->prio || !b->core || !b->n_gseg)
+    return GCAPS_EINVAL;
+  if (b->max_gseg > 0 && (!b->gm_us || !b->ge_us)) return GCAPS_EINVAL;
+  if (policy < GCAPS_POLICY_GCAPS || policy > GCAPS_POLICY_BOTH) return GCAPS_EINVAL;
+  if (wait_mode != GCAPS_WAIT_BUSY && wait_mode != GCAPS_WAIT_SUSPEND) return GCAPS_EINVAL;
+  if (horizon == 0 || horizon > 0x80000000u) return GCAPS_EINVAL;
+  return GCAPS_OK;
 }
 
 int check_gprio_batch(const gcaps_batch *b, int wait_mode, const void *gprio, const void *resp, const void *sched) {
@@ -821,6 +853,56 @@ extern "C" int gcaps_gprio_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, i
   if (rc != GCAPS_OK) return rc;
   if (hipMemcpyAsync(out_resp, d_resp, N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
       hipMemcpyAsync(out_sched, d_sched, N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset,
+                                           int policy, int wait_mode, uint32_t horizon, int64_t *d_out_mort,
+                                           uint32_t *d_out_jobs, uint8_t *d_out_flag) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_simulate(batch, policy, wait_mode, horizon, d_out_mort, d_out_jobs, d_out_flag);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  return run_simulate(ctx, batch, d_offset, policy, wait_mode, horizon, d_out_mort, d_out_jobs, d_out_flag);
+}
+
+extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, int policy,
+                                    int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs,
+                                    uint8_t *out_flag, uint32_t *first_bad_taskset) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_simulate(batch, policy, wait_mode, horizon, out_mort, out_jobs, out_flag);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  const size_t N = batch->n_tasksets, n = batch->n_tasks, P = policy == GCAPS_POLICY_BOTH ? 2 : 1;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t mort_bytes = up(P * N * n * 8), jobs_bytes = up(P * N * n * 4), flag_bytes = up(P * N),
+               off_bytes = up(N * n * 4);
+  gcaps_batch d;
+  rc = upload_batch(ctx, batch, &d, nullptr, nullptr);
+  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(mort_bytes + jobs_bytes + flag_bytes + off_bytes);
+  if (rc != GCAPS_OK) return rc;
+  char *base = (char *)ctx->staging_out.ptr;
+  int64_t *d_mort = (int64_t *)base;
+  uint32_t *d_jobs = (uint32_t *)(base + mort_bytes);
+  uint8_t *d_flag = (uint8_t *)(base + mort_bytes + jobs_bytes);
+  uint32_t *d_off = offset ? (uint32_t *)(base + mort_bytes + jobs_bytes + flag_bytes) : nullptr;
+  if (offset && hipMemcpyAsync(d_off, offset, N * n * 4, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  rc = run_simulate(ctx, &d, d_off, policy, wait_mode, horizon, d_mort, d_jobs, d_flag);
+  if (rc != GCAPS_OK) return rc;
+  rc = gcaps_status(ctx, first_bad_taskset);
+  if (rc != GCAPS_OK) return rc;
+  if (hipMemcpyAsync(out_mort, d_mort, P * N * n * 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_jobs, d_jobs, P * N * n * 4, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+      hipMemcpyAsync(out_flag, d_flag, P * N, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
     return GCAPS_EDEVICE;

@@ -1,0 +1,196 @@
+"""Batched schedule simulation on the GPU (event to event) against the unit-tick simulation oracle, value for
+value: every largest response time (int64), every job count (uint32), every flag, through the C ABI."""
+import numpy as np
+import pytest
+
+from test_gpu_parity import gpu  # noqa: F401 (fixture)
+from test_oracle_sim import PREEMPTION, one_taskset, small_batch
+
+pytestmark = pytest.mark.gpu
+
+GCAPS, RR, BOTH, BUSY, SUSPEND = 1, 2, 3, 0, 1
+
+
+def compare(oracle, B, ctx, batch, horizon, policy=BOTH, waits=(BUSY, SUSPEND), offset=None):
+    flagged = 0
+    for wait in waits:
+        want = oracle.simulate_batch(batch, policy, wait, horizon, offset=offset, threads=16)
+        got = B.gcaps_simulate_batch(ctx, batch, policy, wait, horizon, offset=offset)
+        for name, g, w in zip(("mort", "jobs", "flag"), got, want):
+            bad = np.argwhere(g != w)
+            assert bad.size == 0, (name, wait, bad[:5], g[tuple(bad[0])], w[tuple(bad[0])])
+        flagged += int(want[2].sum())
+    return flagged
+
+
+def test_hand_worked_schedules(gpu):
+    """The two schedules worked out by hand in test_oracle_sim.py, straight against their numbers."""
+    B, ctx, _ = gpu
+    b, off = one_taskset(PREEMPTION, theta=1, eps=1, L=4)
+    for wait in (BUSY, SUSPEND):
+        mort, jobs, flag = B.gcaps_simulate_batch(ctx, b, BOTH, wait, 50, offset=off)
+        assert mort[:, 0].tolist() == [[7, 17], [10, 16]] and (jobs == 1).all() and (flag == 0).all()
+
+
+@pytest.mark.parametrize("seed,N,util", [(1, 333, (0.2, 0.5)), (2, 1000, (0.3, 0.8)), (3, 65, (0.6, 1.0))])
+def test_generated_tasksets(oracle, gpu, seed, N, util):
+    """Several tiles of 64 tasksets and a ragged tail; light load (every job completes) up to overload (jobs
+    still running at their next release: the flag and the outputs up to that instant)."""
+    B, ctx, _ = gpu
+    print(f"seed {seed} N={N} util={util}", flush=True)
+    batch = small_batch(N, seed=seed, util=util)
+    flagged = compare(oracle, B, ctx, batch, 3000)
+    rng = np.random.default_rng(seed)
+    off = rng.integers(0, 300, batch["cpu_us"].shape).astype(np.uint32)
+    flagged += compare(oracle, B, ctx, batch, 2500, offset=off)
+    if util[1] >= 0.8:
+        assert flagged > 0
+    compare(oracle, B, ctx, batch, 1777, policy=GCAPS, waits=(SUSPEND,), offset=off)
+    compare(oracle, B, ctx, batch, 1777, policy=RR, waits=(BUSY,))
+
+
+def shaped(N, seed, n_cores, per_core, S, **kw):
+    from paper_2406_05221_amd import taskgen
+    args = dict(util=(0.1, 0.4), eta=(0, S), share=(0.1, 0.4), period=(60, 600), overhead=(0, 4), slice_us=5)
+    args.update(kw)
+    return taskgen.generate(N, n_cores=n_cores, tasks_per_core=per_core, max_gseg=S, seed=seed, stream=78, **args)
+
+
+def test_shapes(oracle, gpu):
+    """One task; the widest taskset (32 tasks); no GPU segments at all; many segments; slices of one tick; no
+    overheads (updates and switches that take no time)."""
+    B, ctx, _ = gpu
+    for label, batch, horizon in (
+            ("n=1", shaped(130, 1, 1, 1, 2), 2000),
+            ("n=32", shaped(96, 2, 4, 8, 3, util=(0.05, 0.2)), 2500),
+            ("S=0", shaped(100, 3, 2, 4, 0, eta=(0, 0)), 2000),
+            ("S=7", shaped(70, 4, 3, 2, 7, eta=(3, 7), util=(0.05, 0.25)), 2500),
+            ("L=1", shaped(120, 5, 2, 3, 2, slice_us=1), 2000),
+            ("no overhead", shaped(120, 6, 2, 3, 2, overhead=(0, 0)), 2000),
+            ("16 cores", shaped(64, 7, 16, 2, 1), 2000)):
+        print(label, flush=True)
+        compare(oracle, B, ctx, batch, horizon)
+
+
+def test_equal_priorities_and_caller_order(oracle, gpu):
+    """Equal priorities rank by caller index; tasks listed in any order give the same schedule."""
+    B, ctx, _ = gpu
+    batch = small_batch(200, seed=9)
+    ties = dict(batch, prio=(batch["prio"] // 2).astype(np.int32))
+    compare(oracle, B, ctx, ties, 2000)
+    same = dict(batch, prio=np.zeros_like(batch["prio"]))
+    compare(oracle, B, ctx, same, 2000)
+    perm = np.random.default_rng(1).permutation(batch["cpu_us"].shape[1])
+    shuffled = {k: (np.ascontiguousarray(v[:, perm]) if v.ndim >= 2 else v) for k, v in batch.items()}
+    a = B.gcaps_simulate_batch(ctx, batch, BOTH, SUSPEND, 2000)
+    s = B.gcaps_simulate_batch(ctx, shuffled, BOTH, SUSPEND, 2000)
+    assert (a[0][:, :, perm] == s[0]).all() and (a[1][:, :, perm] == s[1]).all() and (a[2] == s[2]).all()
+
+
+def test_large_values(oracle, gpu):
+    """Periods and offsets beyond 2^31: such a task is released once or never within any horizon."""
+    B, ctx, _ = gpu
+    batch = small_batch(64, seed=12)
+    batch["period_us"][:, 0] = 0xFFFFFFFF
+    batch["period_us"][:, 1] = 0x80000001
+    off = np.zeros(batch["cpu_us"].shape, np.uint32)
+    off[::2, 2] = 0xFFFFFFF0
+    off[1::2, 3] = 1999
+    compare(oracle, B, ctx, batch, 2000, offset=off)
+
+
+def test_invalid_arguments(gpu):
+    B, ctx, _ = gpu
+    batch = small_batch(300, seed=13)
+    bad = {k: v.copy() for k, v in batch.items()}
+    bad["period_us"][[77, 250], 2] = 0
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_simulate_batch(ctx, bad, BOTH, BUSY, 100)
+    assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 77
+    bad = {k: v.copy() for k, v in batch.items()}
+    bad["core"][123, 0] = 64
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_simulate_batch(ctx, bad, RR, BUSY, 100)
+    assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 123
+    for kwargs in (dict(policy=0), dict(policy=4), dict(wait=2), dict(horizon=0), dict(horizon=2**31 + 1)):
+        args = dict(policy=BOTH, wait=BUSY, horizon=100)
+        args.update(kwargs)
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_simulate_batch(ctx, batch, args["policy"], args["wait"], args["horizon"])
+        assert e.value.code == B.GCAPS_EINVAL
+    wide = shaped(4, 1, 3, 11, 1)  # 33 tasks: beyond the masks of the kernel
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_simulate_batch(ctx, wide, BOTH, BUSY, 100)
+    assert e.value.code == B.GCAPS_EINVAL
+    # the context still works
+    good = B.gcaps_simulate_batch(ctx, batch, BOTH, BUSY, 100)
+    assert good[0].shape == (2,) + batch["cpu_us"].shape
+
+
+def test_device_entry_point_and_chunks(oracle, monkeypatch):
+    """Device pointers on the caller's stream; a call split into chunks of tasksets (forced by a small chunk size)
+    keeps plane strides and the index of an invalid taskset relative to the whole call; other entry points of the
+    same context before and after."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "128")
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        batch = small_batch(500, seed=14)
+        N, n = batch["cpu_us"].shape
+        off = np.random.default_rng(3).integers(0, 100, (N, n)).astype(np.uint32)
+        want = oracle.simulate_batch(batch, BOTH, SUSPEND, 1500, offset=off, threads=16)
+        want_r = oracle.rta_batch(batch, BOTH, SUSPEND, threads=16)
+        got_r = B.gcaps_rta_batch(ctx, batch, BOTH, SUSPEND)
+        assert (got_r[0] == want_r[0]).all()
+        d = B.to_device(batch)
+        with torch.cuda.stream(stream):
+            d_off = torch.from_numpy(off).cuda()
+            mort = torch.empty((2, N, n), dtype=torch.int64, device="cuda")
+            jobs = torch.empty((2, N, n), dtype=torch.int32, device="cuda")
+            flag = torch.empty((2, N), dtype=torch.uint8, device="cuda")
+            for _ in range(2):
+                B.gcaps_simulate_batch_device(ctx, d, BOTH, SUSPEND, 1500, mort, jobs, flag, d_offset=d_off)
+            B.gcaps_status(ctx)
+        stream.synchronize()
+        assert (mort.cpu().numpy() == want[0]).all()
+        assert (jobs.cpu().numpy().view(np.uint32) == want[1]).all()
+        assert (flag.cpu().numpy() == want[2]).all()
+        got_r = B.gcaps_rta_batch(ctx, batch, BOTH, SUSPEND)
+        assert (got_r[0] == want_r[0]).all() and (got_r[1] == want_r[1]).all()
+        bad = {k: v.copy() for k, v in batch.items()}
+        bad["slice_us"][[300, 444]] = 0
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_simulate_batch(ctx, bad, BOTH, BUSY, 100)
+        assert e.value.first_bad == 300
+        got = B.gcaps_simulate_batch(ctx, batch, BOTH, SUSPEND, 1500, offset=off)
+        assert all((g == w).all() for g, w in zip(got, want))
+    finally:
+        B.gcaps_destroy(ctx)
+
+
+def test_full_size_values_on_sampled_tasksets(oracle, gpu):
+    """Tasksets of the shape and magnitudes of workload 3 (20 tasks on 4 cores, microseconds), lightly loaded so
+    that schedules run on: the whole batch is simulated on the GPU for a second of task time; the oracle, one tick
+    per microsecond, follows a sample of it."""
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    N, horizon = 4096, 1_000_000
+    batch = taskgen.generate(N, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.2, 0.4), eta=(1, 3),
+                             share=(0.10, 0.60), period=(10_000, 100_000), overhead=(50, 500), slice_us=1024,
+                             seed=0, stream=79)
+    sample = np.random.default_rng(8).choice(N, 12, replace=False)
+    sub = {k: np.ascontiguousarray(v[sample]) for k, v in batch.items()}
+    for wait in (BUSY, SUSPEND):
+        print(f"wait {wait}", flush=True)
+        got = B.gcaps_simulate_batch(ctx, batch, BOTH, wait, horizon)
+        want = oracle.simulate_batch(sub, BOTH, wait, horizon, threads=16)
+        assert (got[0][:, sample] == want[0]).all() and (got[1][:, sample] == want[1]).all()
+        assert (got[2][:, sample] == want[2]).all()
+        assert want[2].mean() < 0.5 and want[1].sum() > 1000
+        # at any size: a completed job took at least its own demand, and no more jobs completed than were released
+        C = batch["cpu_us"].astype(np.int64) + batch["gm_us"].sum(2) + batch["ge_us"].sum(2)
+        done = got[1] > 0
+        assert (got[0][done] >= np.broadcast_to(C, got[0].shape)[done]).all()
+        assert (got[1] <= horizon // batch["period_us"] + 1).all()
