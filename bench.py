@@ -82,10 +82,12 @@ def main():
                     help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
                          "HBM byte counters collected over this command)")
     ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
-    ap.add_argument("--row", choices=["rta", "gprio"], default="rta",
+    ap.add_argument("--row", choices=["rta", "gprio", "sim"], default="rta",
                     help="rta (default, the headline): both response-time analyses; gprio: the GPU-segment "
                          "priority assignment (Sec. 4.3 / 5.4) for the tasksets that fail the GCAPS test with "
-                         "GPU priority = CPU priority, as in the procedure of Sec. 6.1")
+                         "GPU priority = CPU priority, as in the procedure of Sec. 6.1; sim: schedule simulation "
+                         "(observed response times, Sec. 6.2) of lightly loaded tasksets of workload 3's shape")
+    ap.add_argument("--horizon", type=int, default=1_000_000, help="--row sim: simulated interval (microseconds)")
     ap.add_argument("--search-all", action="store_true", help="--row gprio: search every taskset, skip none")
     ap.add_argument("--continue-after-miss", action="store_true",
                     help="--row rta: analyse every task, with D_h for the unknown R_h below a miss (not the headline)")
@@ -103,6 +105,8 @@ def main():
     from paper_2406_05221_amd import binding as B, taskgen
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.row == "sim":
+        return bench_sim(args)
     if args.workload == 0:
         N = args.tasksets or 1_000_000
         cores, per_core, S = 4, 5, 3
@@ -313,6 +317,93 @@ def bench_gprio(args, batch, N, cores, per_core, S):
                                     f"workload {args.workload}: {N} tasksets, priority search for every taskset; "
                                     f"headline = slower waiting mode ({head})",
                            tasksets=N, n_tasks=n, max_gseg=S, wait_mode=head, row="gprio"),
+               modes=modes, roofline=roofline, cpu_baseline=cpu)
+    B.gcaps_destroy(ctx)
+    print(json.dumps(out))
+
+
+INT_ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 compute units x 64 lanes per clock (4 SIMDs of 16) x 2.4 GHz
+
+
+def bench_sim(args):
+    """One step = the schedule simulation of one device-resident batch under both GPU policies over
+    --horizon microseconds of task time."""
+    import numpy as np
+    import torch
+    from paper_2406_05221_amd import binding as B, taskgen
+
+    N = args.tasksets or 65_536
+    cores, per_core, S = 4, 5, 3
+    n = cores * per_core
+    batch = taskgen.generate(N, n_cores=cores, tasks_per_core=per_core, max_gseg=S, util=(0.2, 0.4), eta=(1, 3),
+                             share=(0.10, 0.60), period=(10_000, 100_000), overhead=(50, 500), slice_us=1024,
+                             seed=0, stream=79)
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    d = B.to_device(batch)
+    d_mort = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+    d_jobs = torch.empty((2, N, n), dtype=torch.int32, device="cuda:0")
+    d_flag = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    steps = max(1, min(args.steps, 5))
+    warmup = max(1, min(args.warmup, 1))
+    modes = {}
+    for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
+        for _ in range(warmup):
+            B.gcaps_simulate_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, args.horizon, d_mort, d_jobs, d_flag)
+        B.gcaps_status(ctx)
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            starts[k].record(stream)
+            B.gcaps_simulate_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, args.horizon, d_mort, d_jobs, d_flag)
+            stops[k].record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        B.gcaps_status(ctx)
+        events = B.gcaps_last_sim_steps(ctx)
+        dev_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+        modes[name] = dict(wall_ms_per_step=(t1 - t0) * 1e3 / steps, device_ms_per_step=float(np.mean(dev_ms)),
+                           tasksets_per_s=N * steps / (t1 - t0), events_per_step=events,
+                           events_per_s=events / (float(np.mean(dev_ms)) * 1e-3),
+                           jobs_completed=int(d_jobs.sum().item()),
+                           stopped_at_an_overrun=int(d_flag.sum().item()))
+    head = min(modes, key=lambda m: modes[m]["tasksets_per_s"])
+    head_wait = B.GCAPS_WAIT_BUSY if head == "busy" else B.GCAPS_WAIT_SUSPEND
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        sample = min(N, 96)
+        sub = {k: v[:sample] for k, v in batch.items()}
+        t0 = time.perf_counter()
+        want = oracle.simulate_batch(sub, oracle.POLICY_BOTH, head_wait, args.horizon, threads=threads)
+        t_all = time.perf_counter() - t0
+        B.gcaps_simulate_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, head_wait, args.horizon, d_mort, d_jobs, d_flag)
+        B.gcaps_status(ctx)
+        same = bool((d_mort[:, :sample].cpu().numpy() == want[0]).all()
+                    and (d_jobs[:, :sample].cpu().numpy().view(np.uint32) == want[1]).all()
+                    and (d_flag[:, :sample].cpu().numpy() == want[2]).all())
+        cpu = dict(value=sample / t_all, unit="tasksets/s", cores=threads, kind="oracle",
+                   sample=f"first {sample} tasksets of the batch, both policies, {head} mode, one tick per "
+                          f"microsecond, {threads} std::thread workers over tasksets",
+                   gpu_matches_oracle_on_sample=same)
+    m = modes[head]
+    ops_per_event = 6 * n + 40  # per task: release / zero-time test, core arbitration, next-event minimum and charge
+    achieved = m["events_per_step"] * ops_per_event / (m["device_ms_per_step"] * 1e-3) / 1e12
+    roofline = dict(bound="alu", achieved=achieved, peak=INT_ALU_PEAK_TOPS, unit="TOP/s",
+                    frac=achieved / INT_ALU_PEAK_TOPS, traffic=None, kernel="sim::simulate_kernel",
+                    algorithmic_ops_per_event=ops_per_event, events_per_step=m["events_per_step"])
+    out = dict(metric="tasksets simulated/sec (both GPU policies), 1 MI355X", value=m["tasksets_per_s"],
+               unit="tasksets/s", n_gpus=1, steps=steps, warmup=warmup, ms_per_step=m["wall_ms_per_step"],
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="u32", data="synthetic",
+               config=dict(workload=f"{N} tasksets of the shape and magnitudes of workload 3 ({cores} cores x {per_core} "
+                                    f"tasks/core, up to {S} GPU segments/task, microseconds) at a per-core utilisation "
+                                    f"of 0.2-0.4 and periods of 10-100 ms, simulated for {args.horizon} us under GCAPS "
+                                    f"and round-robin; headline = slower waiting mode ({head})",
+                           tasksets=N, n_tasks=n, max_gseg=S, horizon_us=args.horizon, wait_mode=head, row="sim"),
                modes=modes, roofline=roofline, cpu_baseline=cpu)
     B.gcaps_destroy(ctx)
     print(json.dumps(out))

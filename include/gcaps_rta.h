@@ -255,6 +255,13 @@ int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const 
                                 uint8_t *d_out_flag);
 
 /*
+ * Diagnostics of the most recent gcaps_simulate_batch[_device] call (waits for the stream): the number of
+ * steps its lanes took in total, a step being one jump to the next event of a taskset's schedule (Sec. 6.2
+ * defines no such count; it measures the work of the simulation).
+ */
+int gcaps_last_sim_steps(gcaps_ctx *ctx, uint64_t *steps);
+
+/*
  * Optional ordering (off by default) of the tasksets that need the second,
  * full-depth launch: a counting sort by how close to its deadline the last task
  * analysed in the first launch comes (R_k / D_k, 256 buckets, most slack first),

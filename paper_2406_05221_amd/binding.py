@@ -26,7 +26,8 @@ GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
-           "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device"]
+           "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
+           "gcaps_last_sim_steps"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -328,3 +329,16 @@ def gcaps_simulate_batch_device(ctx, dbatch, policy, wait_mode, horizon, d_mort,
                                           d_flag.data_ptr())
     if rc != GCAPS_OK:
         raise GcapsError(rc)
+
+
+_lib.gcaps_last_sim_steps.restype = _int
+_lib.gcaps_last_sim_steps.argtypes = [_p, ctypes.POINTER(ctypes.c_uint64)]
+
+
+def gcaps_last_sim_steps(ctx):
+    """Steps (jumps to the next event) taken by all lanes of the most recent simulation call."""
+    c = ctypes.c_uint64(0)
+    rc = _lib.gcaps_last_sim_steps(ctx, ctypes.byref(c))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    return c.value

@@ -166,6 +166,8 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
     if (first_chunk) {
       status[0] = 0xffffffffu; /* smallest invalid taskset index of the call */
       status[3] = 0;           /* tasksets sent to the 64-bit kernel by earlier chunks */
+      status[4] = 0;           /* steps of the schedule simulation, 64 bits */
+      status[5] = 0;
     } else {
       status[3] += status[1];
     }
@@ -660,7 +662,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     ctx->lds_limit = raised ? (int)want : 65536;
     ctx->lds_total = want > 65536 ? want : 65536;
   }
-  if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, 4 * sizeof(u32), hipHostMallocDefault) != hipSuccess)
+  if (rc == GCAPS_OK && hipHostMalloc((void **)&ctx->host_status, 8 * sizeof(u32), hipHostMallocDefault) != hipSuccess)
     rc = GCAPS_ENOMEM;
   if (rc != GCAPS_OK) {
     (void)hipGetLastError();
@@ -907,6 +909,20 @@ extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, co
     (void)hipGetLastError();
     return GCAPS_EDEVICE;
   }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_last_sim_steps(gcaps_ctx *ctx, uint64_t *steps) {
+  if (!ctx || !steps) return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), 8 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+          hipSuccess ||
+      hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  *steps = (uint64_t)ctx->host_status[sim::kStatusSteps] | (uint64_t)ctx->host_status[sim::kStatusSteps + 1] << 32;
   return GCAPS_OK;
 }
 
