@@ -332,7 +332,7 @@ def bench_sim(args):
     import torch
     from paper_2406_05221_amd import binding as B, taskgen
 
-    N = args.tasksets or 65_536
+    N = args.tasksets or 262_144
     cores, per_core, S = 4, 5, 3
     n = cores * per_core
     batch = taskgen.generate(N, n_cores=cores, tasks_per_core=per_core, max_gseg=S, util=(0.2, 0.4), eta=(1, 3),

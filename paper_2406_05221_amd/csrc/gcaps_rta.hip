@@ -531,7 +531,18 @@ int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset,
   return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
     if (begin_chunk(ctx, c0 == 0) != GCAPS_OK) return (int)GCAPS_EDEVICE;
     ctx->wide_only = true;
-    hipLaunchKernelGGL(sim::simulate_kernel, dim3((sub->n_tasksets + 63u) / 64u, planes), dim3(64), lds, ctx->stream,
+    /* as many single-wavefront workgroups as are resident at once (both planes together); their lanes take
+     * further tasksets as they finish */
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)sim::simulate_kernel, 64, lds) !=
+            hipSuccess || per_cu < 1) {
+      (void)hipGetLastError();
+      per_cu = 1;
+    }
+    u32 blocks = ((u32)ctx->n_cu * (u32)per_cu + planes - 1u) / planes;
+    const u32 tiles = (sub->n_tasksets + 63u) / 64u;
+    if (blocks > tiles) blocks = tiles;
+    hipLaunchKernelGGL(sim::simulate_kernel, dim3(blocks, planes), dim3(64), lds, ctx->stream,
                        *sub, d_offset ? d_offset + c0 * n : nullptr, policy, wait_mode, horizon,
                        (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
                        status_of(ctx), ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
