@@ -1,0 +1,85 @@
+"""Observed response times against the analytic bounds, in the manner of Table 5 (Sec. 6.2), on
+randomly generated tasksets instead of the case study's board:
+
+    python -m paper_2406_05221_amd.pessimism --tasksets 2000 --util 0.3 --horizon-ms 2000
+
+For every taskset drawn by the recipe of Sec. 6.1 (Table 3) and every analysis (GCAPS and the default
+round-robin TSG scheduling, busy-waiting and self-suspension) the GPU library computes the bound R_i of
+every task (response-time analysis) and the largest response time seen in a simulated schedule (synchronous
+release plus a few random release offsets).  Reported per analysis, over the tasks of the tasksets that pass
+the test: the mean and the largest ratio observed / bound, how many tasks were seen to respond later
+than their bound, and how many of those tasksets had a job still running at its next release.  The count of
+tasks above their bound is not expected to be zero: the simulated system charges things the lemmas do not (a
+closing runlist update that waits for the caller's core under GCAPS; the switch after a task's own slice
+under round-robin).
+
+Everything is computed by the GPU library; this module draws inputs, groups them by task count and
+averages."""
+import argparse
+
+import numpy as np
+
+from . import binding as B
+from . import taskgen
+
+ANALYSES = [("gcaps_busy", B.GCAPS_POLICY_GCAPS, B.GCAPS_WAIT_BUSY), ("gcaps_suspend", B.GCAPS_POLICY_GCAPS, B.GCAPS_WAIT_SUSPEND),
+            ("tsg_rr_busy", B.GCAPS_POLICY_RR, B.GCAPS_WAIT_BUSY), ("tsg_rr_suspend", B.GCAPS_POLICY_RR, B.GCAPS_WAIT_SUSPEND)]
+
+
+def study(ctx, groups, horizon, n_offsets=3, seed=0):
+    """groups: {n: (indices, batch)} from ``taskgen.table3``.  Returns {analysis: dict(tasksets, schedulable, tasks,
+    mean_ratio, max_ratio, above_bound, overran)}."""
+    rng = np.random.default_rng(seed)
+    acc = {name: dict(tasksets=0, schedulable=0, ratios=[], above=0, overran=0) for name, _, _ in ANALYSES}
+    for idx, batch in groups.values():
+        fields = {k: v for k, v in batch.items() if k != "best_effort"}
+        N, n = fields["cpu_us"].shape
+        offsets = [None] + [(rng.random((N, n)) * fields["period_us"]).astype(np.uint32) for _ in range(n_offsets)]
+        for name, policy, wait in ANALYSES:
+            resp, sched = B.gcaps_rta_batch(ctx, fields, policy, wait)
+            ok = sched[0].astype(bool)
+            seen = np.zeros((N, n), np.int64)
+            overran = np.zeros(N, bool)
+            for off in offsets:
+                mort, _, flag = B.gcaps_simulate_batch(ctx, fields, policy, wait, horizon, offset=off)
+                seen = np.maximum(seen, mort[0])
+                overran |= flag[0].astype(bool)
+            a = acc[name]
+            a["overran"] += int((overran & ok).sum())
+            a["tasksets"] += N
+            a["schedulable"] += int(ok.sum())
+            bound = resp[0][ok]
+            a["ratios"].append((seen[ok] / np.maximum(bound, 1)).ravel())
+            a["above"] += int((seen[ok] > bound).sum())
+    out = {}
+    for name, a in acc.items():
+        r = np.concatenate(a["ratios"]) if a["ratios"] else np.zeros(0)
+        out[name] = dict(tasksets=a["tasksets"], schedulable=a["schedulable"], tasks=int(r.size),
+                         mean_ratio=float(r.mean()) if r.size else float("nan"),
+                         max_ratio=float(r.max()) if r.size else float("nan"), above_bound=a["above"],
+                         overran=a["overran"])
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--tasksets", type=int, default=2000)
+    ap.add_argument("--util", type=float, default=0.3, help="utilisation per CPU")
+    ap.add_argument("--horizon-ms", type=int, default=2000)
+    ap.add_argument("--offsets", type=int, default=3, help="random release patterns besides the synchronous one")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    ctx = B.gcaps_create(0)
+    try:
+        groups = taskgen.table3(args.tasksets, seed=args.seed, util=(args.util, args.util))
+        res = study(ctx, groups, args.horizon_ms * 1000, n_offsets=args.offsets, seed=args.seed)
+    finally:
+        B.gcaps_destroy(ctx)
+    print(f"{'analysis':16s} {'pass':>12s} {'tasks':>8s} {'mean obs/bound':>15s} {'max obs/bound':>14s} {'obs > bound':>12s} {'overran':>8s}")
+    for name, r in res.items():
+        print(f"{name:16s} {r['schedulable']:>5d}/{r['tasksets']:<6d} {r['tasks']:>8d} {r['mean_ratio']:>15.3f} "
+              f"{r['max_ratio']:>14.3f} {r['above_bound']:>12d} {r['overran']:>8d}")
+
+
+if __name__ == "__main__":
+    main()

@@ -194,3 +194,18 @@ def test_full_size_values_on_sampled_tasksets(oracle, gpu):
         done = got[1] > 0
         assert (got[0][done] >= np.broadcast_to(C, got[0].shape)[done]).all()
         assert (got[1] <= horizon // batch["period_us"] + 1).all()
+
+
+def test_observed_against_bounds_study(gpu):
+    """The study module (observed / bound per analysis on the paper's generation recipe) runs on the library
+    alone; schedulable tasksets exist, observed response times are positive and mostly below their bounds."""
+    from paper_2406_05221_amd import pessimism, taskgen
+    B, ctx, _ = gpu
+    groups = taskgen.table3(300, seed=5, util=(0.25, 0.25))
+    res = pessimism.study(ctx, groups, 1_000_000, n_offsets=1, seed=5)
+    assert set(res) == {name for name, _, _ in pessimism.ANALYSES}
+    for name, r in res.items():
+        print(name, r, flush=True)
+        assert r["tasksets"] == 300 and r["schedulable"] > 0 and r["tasks"] > 0
+        assert 0.0 < r["mean_ratio"] < 1.0
+        assert r["above_bound"] <= r["tasks"] // 20
