@@ -55,18 +55,24 @@ def build_sim(force=False):
     return _SIM_PATH
 
 
+def open_sim_library(path):
+    """Load a build of the simulator's source (the mutation tests load altered copies)."""
+    lib = ctypes.CDLL(path)
+    lib.des_run.restype = ctypes.c_int
+    lib.des_run_gprio.restype = ctypes.c_int
+    u32, i32, p = ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
+    lib.oracle_simulate_batch.restype = ctypes.c_int
+    lib.oracle_simulate_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, p, i32, i32, u32, i32,
+                                          p, p, p, p]
+    return lib
+
+
 def sim_library():
     """The simulator's library (ctypes), built on first use."""
     global _sim
     if _sim is None:
         build_sim()
-        _sim = ctypes.CDLL(_SIM_PATH)
-        _sim.des_run.restype = ctypes.c_int
-        _sim.des_run_gprio.restype = ctypes.c_int
-        u32, i32, p = ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
-        _sim.oracle_simulate_batch.restype = ctypes.c_int
-        _sim.oracle_simulate_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, p, i32, i32, u32, i32,
-                                               p, p, p, p]
+        _sim = open_sim_library(_SIM_PATH)
     return _sim
 
 

@@ -12,6 +12,7 @@ import test_oracle_continue as continue_tests
 import test_oracle_des as des_tests
 import test_oracle_gprio as gprio_tests
 import test_oracle_pins as pin_tests
+import test_oracle_sim as sim_tests
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "rta_oracle.cpp")
@@ -152,3 +153,72 @@ def test_mutant_is_rejected_by_some_pin(oracle, tmp_path, name):
 def test_unmutated_oracle_passes_the_same_pins(oracle):
     for pin in PINS:
         pin(oracle)
+
+
+# ---- the simulation oracle ----------------------------------------------------------------------
+SIM_SRC = os.path.join(ROOT, "oracle", "sim_oracle.cpp")
+
+SIM_MUTANTS = {
+    "no_switch_after_a_completed_segment": ("          if (!ring.empty()) switch_left = theta;\n", "\n"),
+    "rotation_without_switch": ("            ring.push_back(i);\n            switch_left = theta;",
+                                "            ring.push_back(i);\n            switch_left = 0;"),
+    "slice_never_expires": ("        } else if (slice_used == L) {", "        } else if (false) {"),
+    "remove_does_not_hand_over": ("      running = k;\n      if (k >= 0) pending[k] = 0;", "      running = -1;"),
+    "add_does_not_preempt": ("    } else if (higher_g(i, running)) {\n      pending[running] = 1;",
+                             "    } else if (false) {\n      pending[running] = 1;"),
+    "cpu_time_dealt_last_segments_longer": ("d.c.push_back(each + (j < longer ? 1 : 0));",
+                                            "d.c.push_back(each + (j >= parts - longer ? 1 : 0));"),
+    "busy_waiting_leaves_the_core": ("    if (ph == PH_GPU) return wait == 0; /* busy-waiting keeps the core */",
+                                     "    if (ph == PH_GPU) return false;"),
+    "suspended_task_keeps_the_core": ("    if (ph == PH_GPU) return wait == 0; /* busy-waiting keeps the core */",
+                                      "    if (ph == PH_GPU) return true;"),
+    "priority_order_reversed": ("return a.prio > b.prio; });", "return a.prio < b.prio; });"),
+    "response_measured_from_time_zero": ("s.max_resp = std::max(s.max_resp, now_end - s.release);",
+                                         "s.max_resp = std::max(s.max_resp, now_end);"),
+    "overrun_not_detected": ("        if (s.active) {\n          overrun = true;", "        if (false) {\n          overrun = true;"),
+    "planes_swapped": ("      for (int policy = 1; policy <= 2; ++policy) {", "      for (int policy = 2; policy >= 1; --policy) {"),
+    "offsets_ignored": ("        d.offset = offset ? offset[at] : 0;", "        d.offset = 0;"),
+    "update_takes_twice_the_delay": ("        st[g].remaining = eps;", "        st[g].remaining = 2 * eps;"),
+    "gpu_serves_a_pending_task": ("        if (s.active && !s.in_update && s.ops[s.pc].ph == PH_GPU && s.remaining > 0) s.remaining--;",
+                                  "        if (s.active && !s.in_update && s.ops[s.pc].ph == PH_GPU && s.remaining > 0) s.remaining--;\n"
+                                  "        for (int x = 0; x < n; ++x) if (pending[x] && st[x].remaining > 0) st[x].remaining--;"),
+}
+
+SIM_PINS = [
+    sim_tests.test_gcaps_preemption_by_hand,
+    sim_tests.test_round_robin_slices_by_hand,
+    sim_tests.test_cpu_time_is_dealt_to_the_segments_first_segments_longer,
+    sim_tests.test_single_core_cpu_only_equals_the_textbook_recurrence,
+    sim_tests.test_overrun_stops_the_taskset_and_is_flagged,
+    sim_tests.test_simultaneous_arrivals_take_the_gpu_in_priority_order,
+    sim_tests.test_gcaps_bound_misses_a_delayed_closing_update,
+]
+
+
+@pytest.mark.parametrize("name", sorted(SIM_MUTANTS))
+def test_simulator_mutant_is_rejected_by_some_pin(oracle, tmp_path, name):
+    old, new = SIM_MUTANTS[name]
+    src = open(SIM_SRC).read()
+    assert src.count(old) == 1, f"mutation site for {name} not found exactly once"
+    cpp = tmp_path / "mutant.cpp"
+    cpp.write_text(src.replace(old, new))
+    so = tmp_path / "libsimmutant.so"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-fPIC", "-shared", "-pthread", "-o", str(so), str(cpp)], check=True)
+    genuine = oracle.sim_library()
+    oracle._sim = oracle.open_sim_library(str(so))
+    killed_by = None
+    try:
+        for k, pin in enumerate(SIM_PINS):
+            try:
+                pin()
+            except AssertionError:
+                killed_by = k
+                break
+    finally:
+        oracle._sim = genuine
+    assert killed_by is not None, f"no pin notices the planted mistake '{name}'"
+
+
+def test_unmutated_simulator_passes_the_same_pins():
+    for pin in SIM_PINS:
+        pin()

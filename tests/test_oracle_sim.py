@@ -72,6 +72,19 @@ def test_cpu_time_is_dealt_to_the_segments_first_segments_longer():
     assert mort[0, 0].tolist() == [9, 12]  # busy waiting keeps the core: the low task starts at 9
 
 
+def test_simultaneous_arrivals_take_the_gpu_in_priority_order():
+    """Two tasks on two cores reach their GPU segments at the same instant (CPU [0,1) each, G^e = 3, one slice, no
+    switch cost): the higher-priority one enters the ring first whatever the order the caller lists them in.
+    It runs [1,4) and ends at 5; the other runs [4,7) and ends at 8."""
+    low = dict(C=2, T=50, prio=1, core=1, gm=[0], ge=[3])
+    high = dict(C=2, T=50, prio=2, core=0, gm=[0], ge=[3])
+    for tasks, want in (([low, high], [8, 5]), ([high, low], [5, 8])):
+        b, off = one_taskset(tasks, theta=0, eps=0, L=10)
+        for wait in (BUSY, SUSPEND):
+            mort, _, _ = oracle.simulate_batch(b, RR, wait, 50, offset=off)
+            assert mort[0, 0].tolist() == want
+
+
 def classic_response_time(C, T, i):
     R = C[i]
     while True:
