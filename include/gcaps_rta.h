@@ -233,6 +233,10 @@ int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int w
  *     may be NULL;
  *   - events of one instant take effect in decreasing priority, so results do not depend on caller order.
  *   offset     uint32 [n_tasksets][n_tasks] first releases, or NULL: all released at 0
+ *   gprio      int32 [n_tasksets][n_tasks] priorities of the GPU segments (Sec. 4.3; e.g. out_gprio of
+ *              gcaps_gprio_assign_batch), or NULL: the task priorities.  The runlist decisions of
+ *              GCAPS_POLICY_GCAPS compare these (larger = higher; among equal values the higher task priority
+ *              is served first); CPU scheduling and the driver lock go by prio
  *   policy     GCAPS_POLICY_*; BOTH: two output planes, GCAPS then round-robin
  *   horizon    1..2^31: length of the simulated interval
  *   out_mort   int64 [P][n_tasksets][n_tasks]: largest response time among the jobs that completed
@@ -247,11 +251,11 @@ int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int w
  * place; gcaps_simulate_batch_device takes DEVICE pointers, queues the work on the context's stream and
  * returns (errors as gcaps_rta_batch_device; gcaps_status reports on it likewise).
  */
-int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, int policy,
-                         int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag,
+int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, const int32_t *gprio,
+                         int policy, int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag,
                          uint32_t *first_bad_taskset);
-int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset, int policy,
-                                int wait_mode, uint32_t horizon, int64_t *d_out_mort, uint32_t *d_out_jobs,
+int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset,
+                                const int32_t *d_gprio, int policy, int wait_mode, uint32_t horizon, int64_t *d_out_mort, uint32_t *d_out_jobs,
                                 uint8_t *d_out_flag);
 
 /*

@@ -62,7 +62,7 @@ def open_sim_library(path):
     lib.des_run_gprio.restype = ctypes.c_int
     u32, i32, p = ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
     lib.oracle_simulate_batch.restype = ctypes.c_int
-    lib.oracle_simulate_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, p, i32, i32, u32, i32,
+    lib.oracle_simulate_batch.argtypes = [u32, u32, u32, p, p, p, p, p, p, p, p, p, p, p, p, i32, i32, u32, i32,
                                           p, p, p, p]
     return lib
 
@@ -301,7 +301,7 @@ def gprio_rta_batch(batch, gprio, wait_mode, *, options=0, lib=None):
     return resp, sched
 
 
-def simulate_batch(batch, policy_mask, wait_mode, horizon, offset=None, threads=None):
+def simulate_batch(batch, policy_mask, wait_mode, horizon, offset=None, threads=None, gprio=None):
     """Unit-tick simulation of every taskset of a batch (dict of numpy arrays, analysis layout).
     Returns (mort[P,N,n] int64, jobs[P,N,n] uint32, flag[P,N] uint8); raises ValueError with the index of
     the first taskset that breaks the task model."""
@@ -319,6 +319,8 @@ def simulate_batch(batch, policy_mask, wait_mode, horizon, offset=None, threads=
     eta = np.ascontiguousarray(batch["n_gseg"], dtype=np.uint8)
     off = None if offset is None else np.ascontiguousarray(offset, dtype=np.uint32)
     assert off is None or off.shape == (N, n)
+    gp = None if gprio is None else np.ascontiguousarray(gprio, dtype=np.int32)
+    assert gp is None or gp.shape == (N, n)
     mort = np.empty((P, N, n), np.int64)
     jobs = np.empty((P, N, n), np.uint32)
     flag = np.empty((P, N), np.uint8)
@@ -328,7 +330,7 @@ def simulate_batch(batch, policy_mask, wait_mode, horizon, offset=None, threads=
         threads = min(16, os.cpu_count() or 1)
     rc = sim_library().oracle_simulate_batch(N, n, S, ptr(arrs[0]), ptr(arrs[1]), ptr(arrs[2]), ptr(C), ptr(T),
                                              ptr(prio), ptr(core), ptr(eta), ptr(gm), ptr(ge), ptr(off),
-                                             policy_mask, wait_mode, int(horizon), threads, ptr(mort), ptr(jobs),
+                                             ptr(gp), policy_mask, wait_mode, int(horizon), threads, ptr(mort), ptr(jobs),
                                              ptr(flag), ctypes.byref(bad))
     if rc != 0:
         raise ValueError(f"simulate_batch: rc={rc}, first bad taskset {bad.value}")

@@ -406,7 +406,8 @@ extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta,
  * C, T, prio, core, eta^g; per-segment G^m, G^e; one time unit = one tick).  The task model of Sec. 3 gives a
  * job eta^g + 1 CPU segments around its eta^g GPU segments but only their sum C_i; C_i is dealt to them as
  * evenly as integers allow, the first C_i mod (eta^g + 1) segments one tick longer.  offset: [N][n] first
- * release of each task, or null for a synchronous release at time 0.  policy_mask: 1 = GCAPS, 2 = round-robin,
+ * release of each task, or null for a synchronous release at time 0.  gprio: [N][n] priorities of the GPU
+ * segments (Sec. 4.3: the runlist decisions of GCAPS compare these), or null: the task priorities.  policy_mask: 1 = GCAPS, 2 = round-robin,
  * 3 = both (planes in that order).  Outputs per plane: out_mort [N][n] largest response time of the jobs that
  * completed within `horizon` ticks (0 when none did), out_jobs [N][n] their number, out_flag [N] 1 when a job was
  * released while its predecessor was still running (the simulation of that taskset stops there and the outputs
@@ -418,7 +419,7 @@ extern "C" int oracle_simulate_batch(uint32_t N, uint32_t n, uint32_t S, const u
                                      const uint32_t *eps, const uint32_t *L, const uint32_t *C, const uint32_t *T,
                                      const int32_t *prio, const uint8_t *core, const uint8_t *n_gseg,
                                      const uint32_t *gm, const uint32_t *ge, const uint32_t *offset,
-                                     int policy_mask, int wait_mode, uint32_t horizon, int threads,
+                                     const int32_t *gprio, int policy_mask, int wait_mode, uint32_t horizon, int threads,
                                      int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag, int64_t *first_bad) {
   if (first_bad) *first_bad = -1;
   if (N == 0 || n == 0 || n > 255 || S > 255 || !theta || !eps || !L || !C || !T || !prio || !core || !n_gseg ||
@@ -443,7 +444,7 @@ extern "C" int oracle_simulate_batch(uint32_t N, uint32_t n, uint32_t S, const u
         TaskDef &d = tasks[i];
         d.core = core[at];
         d.prio = prio[at];
-        d.gprio = prio[at];
+        d.gprio = gprio ? gprio[at] : prio[at];
         d.T = T[at];
         d.offset = offset ? offset[at] : 0;
         d.eta = n_gseg[at];

@@ -277,14 +277,15 @@ def gcaps_gprio_rta_batch_device(ctx, dbatch, wait_mode, d_gprio, d_resp, d_sche
 
 
 _lib.gcaps_simulate_batch.restype = _int
-_lib.gcaps_simulate_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _int, _int, _u32, _p, _p, _p,
+_lib.gcaps_simulate_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _p, _int, _int, _u32, _p, _p, _p,
                                       ctypes.POINTER(_u32)]
 _lib.gcaps_simulate_batch_device.restype = _int
-_lib.gcaps_simulate_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _int, _int, _u32, _p, _p, _p]
+_lib.gcaps_simulate_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _p, _p, _int, _int, _u32, _p, _p, _p]
 
 
-def gcaps_simulate_batch(ctx, batch, policy, wait_mode, horizon, offset=None):
-    """Host entry point of the schedule simulation.  offset: uint32 [N, n] first releases or None.
+def gcaps_simulate_batch(ctx, batch, policy, wait_mode, horizon, offset=None, gprio=None):
+    """Host entry point of the schedule simulation.  offset: uint32 [N, n] first releases or None; gprio: int32
+    [N, n] GPU-segment priorities or None (the task priorities).
     Returns (mort int64 [P, N, n], jobs uint32 [P, N, n], flag uint8 [P, N])."""
     N, n, S = _shape(batch)
     keep = {}
@@ -296,12 +297,15 @@ def gcaps_simulate_batch(ctx, batch, policy, wait_mode, horizon, offset=None):
         setattr(b, name, a.ctypes.data if a.size else None)
     off = None if offset is None else np.ascontiguousarray(offset, dtype=np.uint32)
     assert off is None or off.shape == (N, n)
+    gp = None if gprio is None else np.ascontiguousarray(gprio, dtype=np.int32)
+    assert gp is None or gp.shape == (N, n)
     P = 2 if policy == GCAPS_POLICY_BOTH else 1
     mort = np.empty((P, N, n), np.int64)
     jobs = np.empty((P, N, n), np.uint32)
     flag = np.empty((P, N), np.uint8)
     bad = _u32(0xFFFFFFFF)
-    rc = _lib.gcaps_simulate_batch(ctx, ctypes.byref(b), None if off is None else off.ctypes.data, policy, wait_mode,
+    rc = _lib.gcaps_simulate_batch(ctx, ctypes.byref(b), None if off is None else off.ctypes.data,
+                                   None if gp is None else gp.ctypes.data, policy, wait_mode,
                                    int(horizon), mort.ctypes.data, jobs.ctypes.data, flag.ctypes.data,
                                    ctypes.byref(bad))
     if rc != GCAPS_OK:
@@ -309,7 +313,8 @@ def gcaps_simulate_batch(ctx, batch, policy, wait_mode, horizon, offset=None):
     return mort, jobs, flag
 
 
-def gcaps_simulate_batch_device(ctx, dbatch, policy, wait_mode, horizon, d_mort, d_jobs, d_flag, d_offset=None):
+def gcaps_simulate_batch_device(ctx, dbatch, policy, wait_mode, horizon, d_mort, d_jobs, d_flag, d_offset=None,
+                                d_gprio=None):
     """Device entry point of the schedule simulation (queued on the context's stream)."""
     N, n = dbatch["cpu_us"].shape
     S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
@@ -324,8 +329,11 @@ def gcaps_simulate_batch_device(ctx, dbatch, policy, wait_mode, horizon, d_mort,
     if d_offset is not None:
         assert d_offset.is_cuda and d_offset.is_contiguous() and d_offset.numel() == N * n
         assert d_offset.element_size() == 4
+    if d_gprio is not None:
+        assert d_gprio.is_cuda and d_gprio.is_contiguous() and d_gprio.numel() == N * n
+        assert d_gprio.element_size() == 4
     rc = _lib.gcaps_simulate_batch_device(ctx, ctypes.byref(b), None if d_offset is None else d_offset.data_ptr(),
-                                          policy, wait_mode, int(horizon), d_mort.data_ptr(), d_jobs.data_ptr(),
+                                          None if d_gprio is None else d_gprio.data_ptr(), policy, wait_mode, int(horizon), d_mort.data_ptr(), d_jobs.data_ptr(),
                                           d_flag.data_ptr())
     if rc != GCAPS_OK:
         raise GcapsError(rc)

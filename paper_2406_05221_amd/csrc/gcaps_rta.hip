@@ -522,7 +522,8 @@ int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const i
 }
 
 /* Schedule simulation (Sec. 6.2: observed response times) of every taskset, one lane each */
-int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset, int policy, int wait_mode,
+int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset, const int32_t *d_gprio, int policy,
+                 int wait_mode,
                  uint32_t horizon, int64_t *d_mort, uint32_t *d_jobs, uint8_t *d_flag) {
   const u64 n = b->n_tasks, N = b->n_tasksets;
   const size_t lds = sim::lds_bytes(b->n_tasks);
@@ -543,7 +544,8 @@ int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset,
     const u32 tiles = (sub->n_tasksets + 63u) / 64u;
     if (blocks > tiles) blocks = tiles;
     hipLaunchKernelGGL(sim::simulate_kernel, dim3(blocks, planes), dim3(64), lds, ctx->stream,
-                       *sub, d_offset ? d_offset + c0 * n : nullptr, policy, wait_mode, horizon,
+                       *sub, d_offset ? d_offset + c0 * n : nullptr, d_gprio ? (const int *)(d_gprio + c0 * n) : nullptr,
+                       policy, wait_mode, horizon,
                        (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
                        status_of(ctx), ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
     return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
@@ -874,17 +876,18 @@ extern "C" int gcaps_gprio_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, i
 }
 
 extern "C" int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset,
-                                           int policy, int wait_mode, uint32_t horizon, int64_t *d_out_mort,
+                                           const int32_t *d_gprio, int policy, int wait_mode, uint32_t horizon, int64_t *d_out_mort,
                                            uint32_t *d_out_jobs, uint8_t *d_out_flag) {
   if (!ctx) return GCAPS_EINVAL;
   int rc = check_simulate(batch, policy, wait_mode, horizon, d_out_mort, d_out_jobs, d_out_flag);
   if (rc != GCAPS_OK) return rc;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  return run_simulate(ctx, batch, d_offset, policy, wait_mode, horizon, d_out_mort, d_out_jobs, d_out_flag);
+  return run_simulate(ctx, batch, d_offset, d_gprio, policy, wait_mode, horizon, d_out_mort, d_out_jobs, d_out_flag);
 }
 
-extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, int policy,
+extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset,
+                                    const int32_t *gprio, int policy,
                                     int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs,
                                     uint8_t *out_flag, uint32_t *first_bad_taskset) {
   if (!ctx) return GCAPS_EINVAL;
@@ -898,7 +901,7 @@ extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, co
                off_bytes = up(N * n * 4);
   gcaps_batch d;
   rc = upload_batch(ctx, batch, &d, nullptr, nullptr);
-  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(mort_bytes + jobs_bytes + flag_bytes + off_bytes);
+  if (rc == GCAPS_OK) rc = ctx->staging_out.reserve(mort_bytes + jobs_bytes + flag_bytes + 2 * off_bytes);
   if (rc != GCAPS_OK) return rc;
   char *base = (char *)ctx->staging_out.ptr;
   int64_t *d_mort = (int64_t *)base;
@@ -909,7 +912,12 @@ extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, co
     (void)hipGetLastError();
     return GCAPS_EDEVICE;
   }
-  rc = run_simulate(ctx, &d, d_off, policy, wait_mode, horizon, d_mort, d_jobs, d_flag);
+  int32_t *d_gprio = gprio ? (int32_t *)(base + mort_bytes + jobs_bytes + flag_bytes + off_bytes) : nullptr;
+  if (gprio && hipMemcpyAsync(d_gprio, gprio, N * n * 4, hipMemcpyHostToDevice, ctx->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  rc = run_simulate(ctx, &d, d_off, d_gprio, policy, wait_mode, horizon, d_mort, d_jobs, d_flag);
   if (rc != GCAPS_OK) return rc;
   rc = gcaps_status(ctx, first_bad_taskset);
   if (rc != GCAPS_OK) return rc;

@@ -47,6 +47,18 @@ def test_gcaps_preemption_by_hand():
         assert mort[0, 0].tolist() == [7, 17] and jobs[0, 0].tolist() == [1, 1] and flag[0, 0] == 0
 
 
+def test_gcaps_with_reversed_gpu_priorities_by_hand():
+    """The same two tasks with the GPU-segment priorities the other way round (Sec. 4.3): the request of the task
+    with the high CPU priority no longer preempts; it joins the pending list at 5 for free.  Low task: GPU [2,12),
+    closing update [12,13), CPU [13,14): response 14.  High task: GPU [13,15), closing update [15,16), CPU [16,17):
+    response 17 - 3 = 14.  Round-robin does not look at priorities."""
+    b, off = one_taskset(PREEMPTION, theta=1, eps=1, L=4)
+    gprio = np.array([[1, 2]], np.int32)
+    for wait in (BUSY, SUSPEND):
+        mort, jobs, flag = oracle.simulate_batch(b, BOTH, wait, 50, offset=off, gprio=gprio)
+        assert mort[:, 0].tolist() == [[14, 14], [10, 16]] and (jobs == 1).all() and (flag == 0).all()
+
+
 def test_round_robin_slices_by_hand():
     """The same two tasks under time-sliced round-robin, L = 4, theta = 1.  Low task on the GPU from 1; the
     high task joins the ring at 5.  The low task's slice that began at 5 ends at 9 (it has had 8 ticks), switch
