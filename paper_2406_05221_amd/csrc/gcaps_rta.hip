@@ -532,23 +532,29 @@ int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset,
   return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
     if (begin_chunk(ctx, c0 == 0) != GCAPS_OK) return (int)GCAPS_EDEVICE;
     ctx->wide_only = true;
-    /* as many single-wavefront workgroups as are resident at once (both planes together); their lanes take
-     * further tasksets as they finish */
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)sim::simulate_kernel, 64, lds) !=
-            hipSuccess || per_cu < 1) {
-      (void)hipGetLastError();
-      per_cu = 1;
+    /* one launch per policy plane, as many single-wavefront workgroups as are resident at once; their lanes take
+     * further tasksets as they finish.  The last launch prepares the status words of the next call. */
+    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+    for (u32 plane = 0; plane < planes; ++plane) {
+      const bool gc = (policy == GCAPS_POLICY_BOTH ? (int)plane + 1 : policy) == GCAPS_POLICY_GCAPS;
+      auto fn = gc ? (busy ? sim::simulate_kernel<true, true> : sim::simulate_kernel<true, false>)
+                   : (busy ? sim::simulate_kernel<false, true> : sim::simulate_kernel<false, false>);
+      int per_cu = 0;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)fn, 64, lds) != hipSuccess || per_cu < 1) {
+        (void)hipGetLastError();
+        per_cu = 1;
+      }
+      u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
+      const u32 tiles = (sub->n_tasksets + 63u) / 64u;
+      if (blocks > tiles) blocks = tiles;
+      hipLaunchKernelGGL(fn, dim3(blocks), dim3(64), lds, ctx->stream, *sub, d_offset ? d_offset + c0 * n : nullptr,
+                         d_gprio ? (const int *)(d_gprio + c0 * n) : nullptr, plane, horizon,
+                         (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
+                         status_of(ctx), ctx->ts_offset, plane + 1 == planes ? ctx->next_status : nullptr,
+                         (u32)fast::kStatusWords);
+      if (hipGetLastError() != hipSuccess) return (int)GCAPS_EDEVICE;
     }
-    u32 blocks = ((u32)ctx->n_cu * (u32)per_cu + planes - 1u) / planes;
-    const u32 tiles = (sub->n_tasksets + 63u) / 64u;
-    if (blocks > tiles) blocks = tiles;
-    hipLaunchKernelGGL(sim::simulate_kernel, dim3(blocks, planes), dim3(64), lds, ctx->stream,
-                       *sub, d_offset ? d_offset + c0 * n : nullptr, d_gprio ? (const int *)(d_gprio + c0 * n) : nullptr,
-                       policy, wait_mode, horizon,
-                       (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
-                       status_of(ctx), ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
-    return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
+    return (int)GCAPS_OK;
   });
 }
 
