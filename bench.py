@@ -27,14 +27,14 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="8c488c051ef7e0b8eeda608dd88f42e3a1aa798049b73edaf599f7c681e641af",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943762022, write_bytes=333292237)
+MEASURED_TRAFFIC = dict(csrc_sha256="09fd02d204d2a925f9e15f5f625a05285a172d4da301b04e38516dfe4e76b7cb",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943760077, write_bytes=333291571)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="8c488c051ef7e0b8eeda608dd88f42e3a1aa798049b73edaf599f7c681e641af",
-                              workload=3, tasksets=1_000_000, fetch_bytes=1235817267, write_bytes=251413248)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="09fd02d204d2a925f9e15f5f625a05285a172d4da301b04e38516dfe4e76b7cb",
+                              workload=3, tasksets=1_000_000, fetch_bytes=1235807539, write_bytes=251420109)
 
 
 def csrc_sha256():
