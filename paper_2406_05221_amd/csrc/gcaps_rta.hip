@@ -64,6 +64,8 @@ struct gcaps_ctx {
   int binning = 0;
   int cont = 0;             /* continue-after-miss (gcaps_set_continue_after_miss) */
   u64 chunk_cap = 0;        /* GCAPS_CHUNK_TASKSETS: smaller chunks than the 32-bit limit needs (testing) */
+  u32 sim_blocks_cap = 0;   /* GCAPS_SIM_BLOCKS: fewer workgroups per simulation launch than fit the GPU (testing:
+                               every lane then takes many tasksets) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
   u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
   size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
@@ -547,6 +549,7 @@ int run_simulate(gcaps_ctx *ctx, const gcaps_batch *b, const uint32_t *d_offset,
       u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
       const u32 tiles = (sub->n_tasksets + 63u) / 64u;
       if (blocks > tiles) blocks = tiles;
+      if (ctx->sim_blocks_cap && blocks > ctx->sim_blocks_cap) blocks = ctx->sim_blocks_cap;
       hipLaunchKernelGGL(fn, dim3(blocks), dim3(64), lds, ctx->stream, *sub, d_offset ? d_offset + c0 * n : nullptr,
                          d_gprio ? (const int *)(d_gprio + c0 * n) : nullptr, plane, horizon,
                          (long long *)(d_mort + c0 * n), d_jobs + c0 * n, d_flag + c0, (size_t)(N * n), (size_t)N,
@@ -642,6 +645,10 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (const char *e = getenv("GCAPS_CHUNK_TASKSETS")) {
     const long v = strtol(e, nullptr, 10);
     if (v >= 1) ctx->chunk_cap = (u64)v;
+  }
+  if (const char *e = getenv("GCAPS_SIM_BLOCKS")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1 && v <= 65535) ctx->sim_blocks_cap = (u32)v;
   }
   if (const char *e = getenv("GCAPS_SCREEN_TASKS")) {
     const long v = strtol(e, nullptr, 10);

@@ -190,6 +190,50 @@ def test_device_entry_point_and_chunks(oracle, monkeypatch):
         B.gcaps_destroy(ctx)
 
 
+def test_lanes_take_further_tasksets(oracle, monkeypatch):
+    """A launch has as many workgroups as fit the GPU; beyond that a lane that is done with a taskset takes the next
+    one nobody has taken.  Forced here with few workgroups: 3 x 64 lanes for 2,500 tasksets of very different
+    lengths (overloaded ones stop early), in two chunks, every value compared."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    monkeypatch.setenv("GCAPS_SIM_BLOCKS", "3")
+    monkeypatch.setenv("GCAPS_CHUNK_TASKSETS", "1500")
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        batch = small_batch(2500, seed=31, util=(0.2, 0.9))
+        off = np.random.default_rng(6).integers(0, 150, batch["cpu_us"].shape).astype(np.uint32)
+        flagged = compare(oracle, B, ctx, batch, 2500, offset=off)
+        assert flagged > 100
+        compare(oracle, B, ctx, batch, 1200, policy=GCAPS, waits=(SUSPEND,))
+        bad = {k: v.copy() for k, v in batch.items()}
+        bad["period_us"][[2222, 2400], 1] = 0
+        with pytest.raises(B.GcapsError) as e:
+            B.gcaps_simulate_batch(ctx, bad, BOTH, BUSY, 100)
+        assert e.value.first_bad == 2222
+    finally:
+        B.gcaps_destroy(ctx)
+
+
+def test_bench_size_on_sampled_tasksets(oracle, gpu):
+    """The batch size and launch configuration that bench.py times (262,144 tasksets of its recipe: more than
+    the lanes that are resident at once), over a tenth of a second of task time; the oracle follows a sample spread over
+    the whole index range, the tasksets that lanes take later included."""
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    N, horizon = 262_144, 100_000
+    batch = taskgen.generate(N, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.2, 0.4), eta=(1, 3),
+                             share=(0.10, 0.60), period=(10_000, 100_000), overhead=(50, 500), slice_us=1024,
+                             seed=0, stream=79)
+    sample = np.sort(np.concatenate([np.random.default_rng(3).choice(N, 44, replace=False), [0, 131_071, 131_072, N - 1]]))
+    sub = {k: np.ascontiguousarray(v[sample]) for k, v in batch.items()}
+    got = B.gcaps_simulate_batch(ctx, batch, BOTH, SUSPEND, horizon)
+    want = oracle.simulate_batch(sub, BOTH, SUSPEND, horizon, threads=16)
+    assert (got[0][:, sample] == want[0]).all() and (got[1][:, sample] == want[1]).all()
+    assert (got[2][:, sample] == want[2]).all()
+    assert B.gcaps_last_sim_steps(ctx) > N
+
+
 def test_full_size_values_on_sampled_tasksets(oracle, gpu):
     """Tasksets of the shape and magnitudes of workload 3 (20 tasks on 4 cores, microseconds), lightly loaded so
     that schedules run on: the whole batch is simulated on the GPU for a second of task time; the oracle, one tick
