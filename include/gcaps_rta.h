@@ -131,7 +131,8 @@ int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wa
  * The launches of a call may be recorded into a HIP graph (stream capture) once a direct call with
  * the same sizes has been made on the context: that call makes the device allocations, a recorded
  * one makes none.  A recorded call depends on no earlier call and can be replayed any number of
- * times, with direct calls in between.
+ * times, with direct calls in between.  The same holds for the other device-resident entry points
+ * (gcaps_gprio_assign_batch_device, gcaps_gprio_rta_batch_device, gcaps_simulate_batch_device).
  */
 int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
                            int64_t *d_out_resp, uint8_t *d_out_sched);

@@ -351,3 +351,40 @@ def test_calls_of_every_kind_interleaved_on_one_context(oracle, gpu, monkeypatch
                     B.gcaps_rta_batch(ctx, bad, 3, SUSPEND)
     finally:
         B.gcaps_destroy(ctx)
+
+
+def test_captured_search_replays(oracle):
+    """The device entry point of the priority search recorded into a HIP graph (after a warm-up call that made the
+    context's allocations) and replayed, with eager calls of other sizes between the replays."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        batch, other = relaxed_workload(3_000, seed=61), relaxed_workload(555, seed=62)
+        want = oracle.gprio_assign_batch(batch, SUSPEND, threads=16)[:3]
+        ref = oracle.gprio_assign_batch(other, BUSY, threads=16)[:3]
+        d = B.to_device(batch)
+        N, n = batch["cpu_us"].shape
+        d_gprio = torch.empty((N, n), dtype=torch.int32, device="cuda:0")
+        d_resp = torch.empty((N, n), dtype=torch.int64, device="cuda:0")
+        d_sched = torch.empty((N,), dtype=torch.uint8, device="cuda:0")
+        B.gcaps_gprio_assign_batch_device(ctx, d, SUSPEND, None, d_gprio, d_resp, d_sched)  # warm-up
+        B.gcaps_status(ctx)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.gcaps_gprio_assign_batch_device(ctx, d, SUSPEND, None, d_gprio, d_resp, d_sched)
+        for k in range(3):
+            d_gprio.fill_(-7)
+            d_resp.fill_(-7)
+            d_sched.fill_(9)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(d_gprio.cpu().numpy(), want[0]) and np.array_equal(d_resp.cpu().numpy(), want[1]), k
+            assert np.array_equal(d_sched.cpu().numpy(), want[2]), k
+            got = B.gcaps_gprio_assign_batch(ctx, other, BUSY)
+            assert all(np.array_equal(g, w) for g, w in zip(got, ref)), k
+        B.gcaps_status(ctx)
+    finally:
+        B.gcaps_destroy(ctx)

@@ -215,6 +215,45 @@ def test_lanes_take_further_tasksets(oracle, monkeypatch):
         B.gcaps_destroy(ctx)
 
 
+def test_captured_simulation_replays(oracle, monkeypatch):
+    """The device entry point recorded into a HIP graph (after a warm-up call that made the context's allocations)
+    and replayed, with eager calls between the replays; few workgroups, so that the hand-out counters are part of
+    what every replay has to find reset."""
+    import torch
+    from paper_2406_05221_amd import binding as B
+    monkeypatch.setenv("GCAPS_SIM_BLOCKS", "5")
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        batch, other = small_batch(1500, seed=41, util=(0.2, 0.8)), small_batch(300, seed=42)
+        want = oracle.simulate_batch(batch, BOTH, BUSY, 2000, threads=16)
+        ref = oracle.simulate_batch(other, BOTH, SUSPEND, 1500, threads=16)
+        d = B.to_device(batch)
+        N, n = batch["cpu_us"].shape
+        mort = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+        jobs = torch.empty((2, N, n), dtype=torch.int32, device="cuda:0")
+        flag = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+        B.gcaps_simulate_batch_device(ctx, d, BOTH, BUSY, 2000, mort, jobs, flag)  # warm-up
+        B.gcaps_status(ctx)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.gcaps_simulate_batch_device(ctx, d, BOTH, BUSY, 2000, mort, jobs, flag)
+        for k in range(3):
+            mort.fill_(-7)
+            jobs.fill_(9)
+            flag.fill_(9)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert (mort.cpu().numpy() == want[0]).all() and (flag.cpu().numpy() == want[2]).all(), k
+            assert (jobs.cpu().numpy().view(np.uint32) == want[1]).all(), k
+            got = B.gcaps_simulate_batch(ctx, other, BOTH, SUSPEND, 1500)
+            assert all((g == w).all() for g, w in zip(got, ref)), k
+        B.gcaps_status(ctx)
+    finally:
+        B.gcaps_destroy(ctx)
+
+
 def test_bench_size_on_sampled_tasksets(oracle, gpu):
     """The batch size and launch configuration that bench.py times (262,144 tasksets of its recipe: more than
     the lanes that are resident at once), over a tenth of a second of task time; the oracle follows a sample spread over
