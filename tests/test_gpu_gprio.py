@@ -386,5 +386,24 @@ def test_captured_search_replays(oracle):
             got = B.gcaps_gprio_assign_batch(ctx, other, BUSY)
             assert all(np.array_equal(g, w) for g, w in zip(got, ref)), k
         B.gcaps_status(ctx)
+        # the analysis for given priorities, recorded and replayed likewise
+        given = np.where(want[2][:, None].astype(bool), want[0], batch["prio"]).astype(np.int32)
+        want_r, want_s = oracle.gprio_rta_batch(batch, given, SUSPEND)
+        d_given = torch.from_numpy(given).cuda()
+        B.gcaps_gprio_rta_batch_device(ctx, d, SUSPEND, d_given, d_resp, d_sched)  # warm-up
+        B.gcaps_status(ctx)
+        graph2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph2, stream=stream):
+            B.gcaps_gprio_rta_batch_device(ctx, d, SUSPEND, d_given, d_resp, d_sched)
+        for k in range(2):
+            d_resp.fill_(-7)
+            d_sched.fill_(9)
+            torch.cuda.synchronize()
+            graph2.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(d_resp.cpu().numpy(), want_r) and np.array_equal(d_sched.cpu().numpy(), want_s), k
+            got = B.gcaps_gprio_assign_batch(ctx, other, BUSY)
+            assert all(np.array_equal(g, w) for g, w in zip(got, ref)), k
+        B.gcaps_status(ctx)
     finally:
         B.gcaps_destroy(ctx)
