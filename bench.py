@@ -82,11 +82,13 @@ def main():
                     help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
                          "HBM byte counters collected over this command)")
     ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
-    ap.add_argument("--row", choices=["rta", "gprio", "sim"], default="rta",
+    ap.add_argument("--row", choices=["rta", "gprio", "sim", "stream"], default="rta",
                     help="rta (default, the headline): both response-time analyses; gprio: the GPU-segment "
                          "priority assignment (Sec. 4.3 / 5.4) for the tasksets that fail the GCAPS test with "
                          "GPU priority = CPU priority, as in the procedure of Sec. 6.1; sim: schedule simulation "
-                         "(observed response times, Sec. 6.2) of lightly loaded tasksets of workload 3's shape")
+                         "(observed response times, Sec. 6.2) of lightly loaded tasksets of workload 3's shape; stream: "
+                         "every step generates a fresh 1M-taskset batch of the workload on the device and analyses it "
+                         "(workload 5's stream of batches without host-to-device copies)")
     ap.add_argument("--horizon", type=int, default=1_000_000, help="--row sim: simulated interval (microseconds)")
     ap.add_argument("--search-all", action="store_true", help="--row gprio: search every taskset, skip none")
     ap.add_argument("--continue-after-miss", action="store_true",
@@ -107,6 +109,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if args.row == "sim":
         return bench_sim(args)
+    if args.row == "stream":
+        return bench_stream(args)
     if args.workload == 0:
         N = args.tasksets or 1_000_000
         cores, per_core, S = 4, 5, 3
@@ -318,6 +322,90 @@ def bench_gprio(args, batch, N, cores, per_core, S):
                                     f"headline = slower waiting mode ({head})",
                            tasksets=N, n_tasks=n, max_gseg=S, wait_mode=head, row="gprio"),
                modes=modes, roofline=roofline, cpu_baseline=cpu)
+    B.gcaps_destroy(ctx)
+    print(json.dumps(out))
+
+
+def bench_stream(args):
+    """One step = one fresh batch of the workload generated on the device (taskset indices continue from
+    batch to batch) and analysed under both policies: the stream of batches of workload 5 with no host-to-device
+    copy.  The batch of the last timed step is copied back and analysed by the oracle."""
+    import numpy as np
+    import torch
+    from paper_2406_05221_amd import binding as B, taskgen
+
+    k = args.workload if args.workload in (1, 2, 3, 4, 5) else 5
+    N = args.tasksets or min(taskgen.CONFIG_SIZES[k], 1_000_000)
+    cores, per_core, S = taskgen.CONFIG_SHAPES[k]
+    n = cores * per_core
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    d_resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+    d_sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+    total = args.warmup + args.steps
+    # per-taskset parameters of the workload (its sweep point or grid cell) for every batch: resident before timing
+    specs = []
+    for bidx in range(total):
+        _, params = taskgen.config_params(k, N, first_index=bidx * N)
+        specs.append({key: (torch.from_numpy(v.view(np.int32) if v.dtype == np.uint32 else v).cuda()
+                            if isinstance(v, np.ndarray) else v) for key, v in params.items()})
+    torch.cuda.synchronize()
+
+    def generate(params, out):
+        # device tensors stand in for the per-taskset arrays: marshal them as the binding does for numpy arrays
+        fixed = {key: v for key, v in params.items() if isinstance(v, torch.Tensor)}
+        plain = {key: ((0, 0) if key != "slice_us" else 1) if key in fixed else v for key, v in params.items()}
+        return B.gcaps_taskgen_device(ctx, N, out=out, fixed=fixed, **plain)
+
+    wait = B.GCAPS_WAIT_SUSPEND
+    d = None
+    with torch.cuda.stream(stream):
+        for bidx in range(args.warmup):
+            d = generate(specs[bidx], d)
+            B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            starts[s].record(stream)
+            d = generate(specs[args.warmup + s], d)
+            B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, d_resp, d_sched)
+            stops[s].record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        B.gcaps_status(ctx)
+    dev_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, stops)]))
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        host = B.to_host(d)
+        t0c = time.perf_counter()
+        want_r, want_s, _ = oracle.rta_batch(host, oracle.POLICY_BOTH, wait, threads=threads)
+        t_all = time.perf_counter() - t0c
+        same = bool((d_resp.cpu().numpy() == want_r).all() and (d_sched.cpu().numpy() == want_s).all())
+        cpu = dict(value=N / t_all, unit="tasksets/s", cores=threads, kind="oracle",
+                   sample=f"the last batch of the stream ({N} tasksets, copied back), analysis only, "
+                          f"{threads} std::thread workers over tasksets", gpu_matches_oracle_on_sample=same)
+    inputs = 3 * 4 + n * (4 * 4 + 2 * 1) + n * S * 2 * 4
+    alg_bytes = N * (inputs + algorithmic_bytes_per_taskset(n, S, 2))  # written by the generator; read and answered
+    achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    out = dict(metric="tasksets generated on the device and analysed/sec (GCAPS + round-robin), 1 MI355X",
+               value=N * args.steps / (t1 - t0), unit="tasksets/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=(t1 - t0) * 1e3 / args.steps, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="u32", data="synthetic",
+               config=dict(workload=f"workload {k}: a stream of {args.steps} batches of {N} tasksets, {cores} cores x "
+                                    f"{per_core} tasks/core, up to {S} GPU segments/task; each generated on the device "
+                                    f"and analysed under both policies, self-suspension",
+                           tasksets=N, n_tasks=n, max_gseg=S, wait_mode="suspend", row="stream"),
+               device_ms_per_step=dev_ms,
+               roofline=dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                             frac=achieved / HBM_PEAK_GBS, traffic=None,
+                             kernel="gen::generate_kernel + gcaps_rta_batch_device (all launches of one step)",
+                             algorithmic_bytes_per_step=alg_bytes),
+               cpu_baseline=cpu)
     B.gcaps_destroy(ctx)
     print(json.dumps(out))
 

@@ -260,6 +260,39 @@ int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const 
                                 uint8_t *d_out_flag);
 
 /*
+ * Synthetic input generated on the device (the evaluation of Sec. 6.1 analyses streams of randomly generated
+ * tasksets; generating a batch where it is analysed saves the host-to-device copy).  The recipe is that of the
+ * host generator of this package: per core a utilisation drawn from [util_lo, util_hi] and split over the
+ * tasks of the core by UUniFast; per task a log-uniform period in [period_lo, period_hi] (D = T), eta^g in
+ * [eta_lo, eta_hi], C + G = u T, the share G / (C + G) drawn from [share_lo, share_hi] and dealt evenly to the
+ * segments, each half G^m and half G^e; theta = eps drawn from [overhead_lo, overhead_hi]; L = slice_us;
+ * rate-monotonic priorities over the taskset; tasks i*tasks_per_core .. on core i.  Taskset k of the call uses
+ * the random stream (seed, stream, first_index + k): a batch can be generated in pieces and regenerated.
+ * The *_fixed members, if not NULL, are DEVICE arrays [n_tasksets] that fix a value per taskset instead of
+ * drawing it.  Integer decisions are taken from double-precision values computed with the device's math library;
+ * they can differ by one unit from the host generator's in rare elements.
+ * batch: sizes and DEVICE pointers of the buffers to fill (n_tasks must equal n_cores * tasks_per_core, eta_hi
+ * <= max_gseg; n_cseg is ignored); the call queues one kernel on the context's stream and returns.
+ * Errors: GCAPS_EINVAL for null pointers or inconsistent ranges, GCAPS_EDEVICE.
+ */
+typedef struct {
+  uint64_t seed, stream, first_index;
+  uint32_t n_cores, tasks_per_core;
+  double util_lo, util_hi;
+  const double *util_fixed;
+  uint32_t eta_lo, eta_hi;
+  double share_lo, share_hi;
+  const double *share_fixed;
+  uint32_t period_lo, period_hi;
+  uint32_t overhead_lo, overhead_hi;
+  const uint32_t *overhead_fixed;
+  uint32_t slice_us;
+  const uint32_t *slice_fixed;
+} gcaps_taskgen_spec;
+
+int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *spec, const gcaps_batch *batch);
+
+/*
  * Diagnostics of the most recent gcaps_simulate_batch[_device] call (waits for the stream): the number of
  * steps its lanes took in total, a step being one jump to the next event of a taskset's schedule (Sec. 6.2
  * defines no such count; it measures the work of the simulation).

@@ -27,7 +27,7 @@ EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
            "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
-           "gcaps_last_sim_steps"]
+           "gcaps_last_sim_steps", "gcaps_taskgen_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -350,3 +350,79 @@ def gcaps_last_sim_steps(ctx):
     if rc != GCAPS_OK:
         raise GcapsError(rc)
     return c.value
+
+
+class gcaps_taskgen_spec(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("stream", ctypes.c_uint64), ("first_index", ctypes.c_uint64),
+                ("n_cores", _u32), ("tasks_per_core", _u32), ("util_lo", ctypes.c_double), ("util_hi", ctypes.c_double),
+                ("util_fixed", _p), ("eta_lo", _u32), ("eta_hi", _u32), ("share_lo", ctypes.c_double),
+                ("share_hi", ctypes.c_double), ("share_fixed", _p), ("period_lo", _u32), ("period_hi", _u32),
+                ("overhead_lo", _u32), ("overhead_hi", _u32), ("overhead_fixed", _p), ("slice_us", _u32),
+                ("slice_fixed", _p)]
+
+
+_lib.gcaps_taskgen_device.restype = _int
+_lib.gcaps_taskgen_device.argtypes = [_p, ctypes.POINTER(gcaps_taskgen_spec), ctypes.POINTER(gcaps_batch)]
+
+
+def gcaps_taskgen_device(ctx, n_tasksets, *, n_cores, tasks_per_core, max_gseg, util, eta, share, period, overhead,
+                         slice_us, seed=0, stream=0, first_index=0, out=None, device="cuda:0", fixed=None):
+    """Generates a batch on the device with the parameters of ``taskgen.generate`` (a numpy array [N] in place of
+    a range fixes the value per taskset; it is copied to the device).  Returns the dict of torch device tensors
+    that ``gcaps_rta_batch_device`` and the other device entry points take; `out` reuses the tensors of an
+    earlier call of the same shape.  `fixed`: per-taskset values that are already on the device, as a dict of
+    torch tensors [N] keyed util / share (float64), overhead / slice_us (uint32 bits in int32); the caller keeps them
+    alive until the work has run.  The work is queued on the context's stream."""
+    import torch
+    N, n, S = int(n_tasksets), n_cores * tasks_per_core, int(max_gseg)
+    if out is None:
+        shapes = {1: (N,), 2: (N, n), 3: (N, n, S)}
+        kinds = {np.uint32: torch.int32, np.int32: torch.int32, np.uint8: torch.uint8}  # uint32 bits in int32 tensors
+        out = {name: torch.empty(shapes[ndim], dtype=kinds[dtype], device=device) for name, dtype, ndim in _FIELDS}
+    b = gcaps_batch(n_tasksets=N, n_tasks=n, max_gseg=S)
+    for name, _, _ in _FIELDS:
+        t = out[name]
+        assert t.is_cuda and t.is_contiguous(), name
+        setattr(b, name, t.data_ptr() if t.numel() else None)
+    keep = []
+
+    fixed = fixed or {}
+
+    def rng_or_fixed(x, dtype, key=None):
+        if key in fixed:
+            t = fixed[key]
+            assert t.is_cuda and t.is_contiguous() and t.shape == (N,) and t.element_size() == np.dtype(dtype).itemsize
+            return (0, 0), t.data_ptr()
+        if isinstance(x, np.ndarray):
+            a = np.ascontiguousarray(x, dtype=dtype)
+            t = torch.from_numpy(a.view(np.int32) if dtype == np.uint32 else a).to(device)
+            assert t.shape == (N,)
+            keep.append(t)
+            return (0, 0), t.data_ptr()
+        return x, None
+
+    (u_lo, u_hi), u_fix = rng_or_fixed(util, np.float64, "util")
+    (s_lo, s_hi), s_fix = rng_or_fixed(share, np.float64, "share")
+    (o_lo, o_hi), o_fix = rng_or_fixed(overhead, np.uint32, "overhead")
+    if isinstance(slice_us, np.ndarray) or "slice_us" in fixed:
+        (_, _), l_fix = rng_or_fixed(slice_us, np.uint32, "slice_us")
+        l_val = 0
+    else:
+        l_fix, l_val = None, int(slice_us)
+    spec = gcaps_taskgen_spec(seed=seed, stream=stream, first_index=first_index, n_cores=n_cores,
+                              tasks_per_core=tasks_per_core, util_lo=float(u_lo), util_hi=float(u_hi), util_fixed=u_fix,
+                              eta_lo=eta[0], eta_hi=eta[1], share_lo=float(s_lo), share_hi=float(s_hi),
+                              share_fixed=s_fix, period_lo=period[0], period_hi=period[1], overhead_lo=int(o_lo),
+                              overhead_hi=int(o_hi), overhead_fixed=o_fix, slice_us=l_val, slice_fixed=l_fix)
+    rc = _lib.gcaps_taskgen_device(ctx, ctypes.byref(spec), ctypes.byref(b))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    if keep:
+        torch.cuda.synchronize()  # the per-taskset arrays must outlive the kernel that reads them
+    return out
+
+
+def to_host(dbatch):
+    """The numpy form of a device batch (uint32 fields are kept in int32 tensors on the device)."""
+    return {name: (dbatch[name].cpu().numpy().view(np.uint32) if dtype == np.uint32 else dbatch[name].cpu().numpy())
+            for name, dtype, _ in _FIELDS}

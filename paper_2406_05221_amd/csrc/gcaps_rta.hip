@@ -21,6 +21,7 @@
 #include "gprio_wide.hip.inc"
 #include "gprio_fast.hip.inc"
 #include "sim.hip.inc"
+#include "taskgen_device.hip.inc"
 
 namespace {
 
@@ -942,6 +943,26 @@ extern "C" int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, co
     return GCAPS_EDEVICE;
   }
   return GCAPS_OK;
+}
+
+extern "C" int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *sp, const gcaps_batch *b) {
+  if (!ctx || !sp || !b) return GCAPS_EINVAL;
+  if (b->n_tasksets == 0 || b->n_tasks == 0 || b->n_tasks > 255 || b->max_gseg > 255) return GCAPS_EINVAL;
+  if (!b->theta_us || !b->eps_us || !b->slice_us || !b->cpu_us || !b->period_us || !b->deadline_us || !b->prio ||
+      !b->core || !b->n_gseg || (b->max_gseg > 0 && (!b->gm_us || !b->ge_us)))
+    return GCAPS_EINVAL;
+  if (sp->n_cores == 0 || sp->n_cores > 255 || sp->tasks_per_core == 0 ||
+      (uint64_t)sp->n_cores * sp->tasks_per_core != b->n_tasks || sp->eta_lo > sp->eta_hi ||
+      sp->eta_hi > b->max_gseg || sp->period_lo == 0 || sp->period_lo > sp->period_hi ||
+      sp->overhead_lo > sp->overhead_hi || !(sp->util_lo <= sp->util_hi) || !(sp->share_lo <= sp->share_hi) ||
+      (!sp->slice_fixed && sp->slice_us == 0))
+    return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  hipLaunchKernelGGL(gen::generate_kernel, dim3((b->n_tasksets + 63u) / 64u), dim3(64),
+                     (size_t)b->n_tasks * 64 * sizeof(u32), ctx->stream, *b, *sp,
+                     (u32 *)nullptr, 0u);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
 extern "C" int gcaps_last_sim_steps(gcaps_ctx *ctx, uint64_t *steps) {

@@ -95,34 +95,40 @@ _GRID5 = [(u, g, o, l) for u in (0.3, 0.5, 0.7, 0.9) for g in (0.1, 0.3, 0.5) fo
           for l in (512, 1024, 2048)]
 
 
+def config_params(k, n_tasksets=None, *, first_index=0, seed=0):
+    """The generation parameters of workload k (1..5) as keyword arguments of ``generate`` (and of the
+    device-side generator of the GPU library, which takes the same ones), with n_tasksets first."""
+    N = CONFIG_SIZES[k] if n_tasksets is None else int(n_tasksets)
+    cores, per_core, S = CONFIG_SHAPES[k]
+    idx = np.arange(first_index, first_index + N, dtype=np.int64)
+    common = dict(n_cores=cores, tasks_per_core=per_core, max_gseg=S, seed=seed, stream=k, first_index=first_index)
+    if k == 1:
+        return N, dict(util=(0.4, 0.4), eta=(1, 1), share=(0.10, 0.30), period=(10_000, 100_000),
+                       overhead=(200, 200), slice_us=1024, **common)
+    if k == 2:
+        util = (0.1 * (1 + (idx // 1000) % 9)).astype(np.float64)
+        return N, dict(util=util, eta=(1, 3), share=(0.10, 0.50), period=(1_000, 500_000),
+                       overhead=(200, 200), slice_us=1024, **common)
+    if k == 3:
+        return N, dict(util=(0.2, 0.8), eta=(1, 3), share=(0.10, 0.60), period=(1_000, 1_000_000),
+                       overhead=(50, 500), slice_us=1024, **common)
+    if k == 4:
+        return N, dict(util=(0.5, 0.9), eta=(1, 5), share=(0.20, 0.70), period=(500, 2_000_000),
+                       overhead=(300, 300), slice_us=2048, **common)
+    if k == 5:
+        cell = np.array(_GRID5, dtype=np.float64)[idx % len(_GRID5)]
+        return N, dict(util=np.ascontiguousarray(cell[:, 0]), eta=(1, 4),
+                       share=np.ascontiguousarray(cell[:, 1]), period=(1_000, 1_000_000),
+                       overhead=cell[:, 2].astype(np.uint32), slice_us=cell[:, 3].astype(np.uint32), **common)
+    raise ValueError(f"unknown workload {k}")
+
+
 def config(k, n_tasksets=None, *, first_index=0, seed=0, threads=None):
     """Workload k (1..5).  n_tasksets defaults to the workload's full size; first_index selects
     where in the workload's taskset sequence the batch starts (workload 5 is streamed in
     batches; its grid cell and workload 2's sweep point are functions of the taskset index)."""
-    N = CONFIG_SIZES[k] if n_tasksets is None else int(n_tasksets)
-    cores, per_core, S = CONFIG_SHAPES[k]
-    idx = np.arange(first_index, first_index + N, dtype=np.int64)
-    common = dict(n_cores=cores, tasks_per_core=per_core, max_gseg=S, seed=seed, stream=k,
-                  first_index=first_index, threads=threads)
-    if k == 1:
-        return generate(N, util=(0.4, 0.4), eta=(1, 1), share=(0.10, 0.30), period=(10_000, 100_000),
-                        overhead=(200, 200), slice_us=1024, **common)
-    if k == 2:
-        util = (0.1 * (1 + (idx // 1000) % 9)).astype(np.float64)
-        return generate(N, util=util, eta=(1, 3), share=(0.10, 0.50), period=(1_000, 500_000),
-                        overhead=(200, 200), slice_us=1024, **common)
-    if k == 3:
-        return generate(N, util=(0.2, 0.8), eta=(1, 3), share=(0.10, 0.60), period=(1_000, 1_000_000),
-                        overhead=(50, 500), slice_us=1024, **common)
-    if k == 4:
-        return generate(N, util=(0.5, 0.9), eta=(1, 5), share=(0.20, 0.70), period=(500, 2_000_000),
-                        overhead=(300, 300), slice_us=2048, **common)
-    if k == 5:
-        cell = np.array(_GRID5, dtype=np.float64)[idx % len(_GRID5)]
-        return generate(N, util=np.ascontiguousarray(cell[:, 0]), eta=(1, 4),
-                        share=np.ascontiguousarray(cell[:, 1]), period=(1_000, 1_000_000),
-                        overhead=cell[:, 2].astype(np.uint32), slice_us=cell[:, 3].astype(np.uint32), **common)
-    raise ValueError(f"unknown workload {k}")
+    N, params = config_params(k, n_tasksets, first_index=first_index, seed=seed)
+    return generate(N, threads=threads, **params)
 
 
 # ---- the recipe of the paper's schedulability experiments (Sec. 6.1, Table 3) ---------------------
