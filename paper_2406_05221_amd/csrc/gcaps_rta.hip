@@ -959,9 +959,18 @@ extern "C" int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *sp
     return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  hipLaunchKernelGGL(gen::generate_kernel, dim3((b->n_tasksets + 63u) / 64u), dim3(64),
-                     (size_t)b->n_tasks * 64 * sizeof(u32), ctx->stream, *b, *sp,
-                     (u32 *)nullptr, 0u);
+  /* stores gathered through LDS where a taskset's per-task values fit; else the plain kernel */
+  const u32 S = b->max_gseg;
+  u32 tb = S ? 16u / S : 1u;
+  if (tb < 1u) tb = 1u;
+  if (tb > b->n_tasks) tb = b->n_tasks;
+  const size_t staged = gen::staged_lds_bytes(b->n_tasks, S, tb);
+  const dim3 grid((b->n_tasksets + 63u) / 64u), block(64);
+  if (staged <= (size_t)ctx->lds_limit)
+    hipLaunchKernelGGL(gen::generate_staged_kernel, grid, block, staged, ctx->stream, *b, *sp, tb);
+  else
+    hipLaunchKernelGGL(gen::generate_kernel, grid, block, (size_t)b->n_tasks * 64 * sizeof(u32), ctx->stream, *b, *sp,
+                       (u32 *)nullptr, 0u);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
