@@ -27,14 +27,14 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="15e35bb0187683161f0e346d1d738de5ae496aa57d0a94c6a98366271d626450",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943850803, write_bytes=333290854)
+MEASURED_TRAFFIC = dict(csrc_sha256="2e6b09f412999c309fff2a85b006cd52d6f6eab17efb18d5757ac9f32a405f23",
+                        workload=3, tasksets=1_000_000, fetch_bytes=943826534, write_bytes=333292339)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="15e35bb0187683161f0e346d1d738de5ae496aa57d0a94c6a98366271d626450",
-                              workload=3, tasksets=1_000_000, fetch_bytes=1235831296, write_bytes=251410586)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="2e6b09f412999c309fff2a85b006cd52d6f6eab17efb18d5757ac9f32a405f23",
+                              workload=3, tasksets=1_000_000, fetch_bytes=1235789926, write_bytes=251419494)
 
 
 def csrc_sha256():
