@@ -253,11 +253,11 @@ int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int w
  * returns (errors as gcaps_rta_batch_device; gcaps_status reports on it likewise).
  */
 int gcaps_simulate_batch(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *offset, const int32_t *gprio,
-                         int policy, int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs, uint8_t *out_flag,
-                         uint32_t *first_bad_taskset);
+                         int policy, int wait_mode, uint32_t horizon, int64_t *out_mort, uint32_t *out_jobs,
+                         uint8_t *out_flag, uint32_t *first_bad_taskset);
 int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const uint32_t *d_offset,
-                                const int32_t *d_gprio, int policy, int wait_mode, uint32_t horizon, int64_t *d_out_mort, uint32_t *d_out_jobs,
-                                uint8_t *d_out_flag);
+                                const int32_t *d_gprio, int policy, int wait_mode, uint32_t horizon,
+                                int64_t *d_out_mort, uint32_t *d_out_jobs, uint8_t *d_out_flag);
 
 /*
  * Synthetic input generated on the device (the evaluation of Sec. 6.1 analyses streams of randomly generated
