@@ -72,6 +72,43 @@ def test_shapes(oracle, gpu):
         compare(oracle, B, ctx, batch, horizon)
 
 
+def raw_batch(N, n, S, seed, n_cores):
+    """Tasksets drawn field by field, with empty CPU time, empty launch and GPU parts, slots beyond eta^g filled
+    with junk, repeated priorities: what the generator never produces."""
+    rng = np.random.default_rng(seed)
+    return dict(theta_us=rng.integers(0, 3, N).astype(np.uint32), eps_us=rng.integers(0, 3, N).astype(np.uint32),
+                slice_us=rng.integers(1, 5, N).astype(np.uint32),
+                cpu_us=rng.integers(0, 7, (N, n)).astype(np.uint32),
+                period_us=rng.integers(20, 90, (N, n)).astype(np.uint32),
+                deadline_us=np.ones((N, n), np.uint32),
+                prio=rng.integers(0, n, (N, n)).astype(np.int32),
+                core=rng.integers(0, n_cores, (N, n)).astype(np.uint8),
+                n_gseg=rng.integers(0, S + 1, (N, n)).astype(np.uint8),
+                gm_us=rng.integers(0, 3, (N, n, S)).astype(np.uint32),
+                ge_us=rng.integers(0, 6, (N, n, S)).astype(np.uint32))
+
+
+def test_empty_phases_and_junk_in_unused_slots(oracle, gpu):
+    """Phases of length zero chain zero-time transitions (a job can consist of nothing at all); updates that cost
+    nothing; priorities that repeat; values in the segment slots beyond eta^g must not matter."""
+    B, ctx, _ = gpu
+    for seed, (n, S, cores) in enumerate([(5, 3, 2), (8, 2, 3), (3, 4, 1), (12, 1, 4)]):
+        batch = raw_batch(700, n, S, seed, cores)
+        off = np.random.default_rng(seed).integers(0, 40, batch["cpu_us"].shape).astype(np.uint32)
+        print(f"n={n} S={S}", flush=True)
+        compare(oracle, B, ctx, batch, 700, offset=off)
+        compare(oracle, B, ctx, batch, 500)
+        gp = np.random.default_rng(seed + 9).integers(0, 3, batch["cpu_us"].shape).astype(np.int32)
+        compare(oracle, B, ctx, batch, 500, policy=GCAPS, gprio=gp)
+        clean = {k: v.copy() for k, v in batch.items()}
+        unused = np.arange(S)[None, None, :] >= batch["n_gseg"][:, :, None]
+        clean["gm_us"][unused] = 0
+        clean["ge_us"][unused] = 0
+        a = B.gcaps_simulate_batch(ctx, batch, BOTH, SUSPEND, 500)
+        c = B.gcaps_simulate_batch(ctx, clean, BOTH, SUSPEND, 500)
+        assert all((x == y).all() for x, y in zip(a, c))
+
+
 def test_equal_priorities_and_caller_order(oracle, gpu):
     """Equal priorities rank by caller index; tasks listed in any order give the same schedule."""
     B, ctx, _ = gpu
