@@ -352,3 +352,35 @@ def test_observed_against_bounds_study(gpu):
         assert r["schedulable"] > 0 and r["tasks"] > 0
         assert 0.0 < r["mean_ratio"] < 1.0
         assert r["above_bound"] <= r["tasks"] // 20
+
+
+def test_bounds_hold_at_scale(gpu):
+    """The domination pin of the analysis (no job of a schedulable taskset responds later than its bound) on 60,000
+    tasksets with microsecond-scale values instead of a few hundred tiny ones: bounds and schedules both from the
+    library.  GCAPS on tasksets whose GPU-using tasks lead their cores, round-robin at theta = 0 (the two things
+    the lemmas do not charge are excluded, as in test_oracle_sim.py)."""
+    from paper_2406_05221_amd import taskgen
+    from test_oracle_sim import gpu_tasks_lead_their_cores
+    B, ctx, _ = gpu
+    N = 60_000
+    batch = taskgen.generate(N, n_cores=3, tasks_per_core=3, max_gseg=2, util=(0.15, 0.5), eta=(0, 2),
+                             share=(0.1, 0.5), period=(5_000, 50_000), overhead=(20, 300), slice_us=1024,
+                             seed=3, stream=81)
+    rr = dict(batch, theta_us=np.zeros_like(batch["theta_us"]))
+    rng = np.random.default_rng(12)
+    checked = 0
+    for policy, b in ((GCAPS, batch), (RR, rr)):
+        for wait in (BUSY, SUSPEND):
+            resp, sched = B.gcaps_rta_batch(ctx, b, policy, wait)
+            ok = sched[0].astype(bool)
+            if policy == GCAPS:
+                ok &= gpu_tasks_lead_their_cores(b)
+            for trial in range(2):
+                off = None if trial == 0 else (rng.random(b["cpu_us"].shape) * b["period_us"]).astype(np.uint32)
+                mort, jobs, flag = B.gcaps_simulate_batch(ctx, b, policy, wait, 400_000, offset=off)
+                assert not flag[0][ok].any()
+                worse = mort[0][ok] > resp[0][ok]
+                assert not worse.any(), (policy, wait, trial, int(worse.sum()))
+                assert (jobs[0][ok] >= 1).all()
+            checked += int(ok.sum())
+    assert checked > 15_000
