@@ -282,6 +282,75 @@ def test_batch_matches_single_calls_and_honours_skip(oracle):
             assert (g1 == gp[s]).all() and (r1 == resp[s]).all() and s1 == sched[s]
 
 
+def admissible_levels(rng, prio, core):
+    """GPU priority levels 1..n drawn at random among those that keep, on every core, the order of
+    the CPU priorities (Sec. 4.3): the levels that fall on a core are dealt to its tasks by CPU priority."""
+    n = len(prio)
+    levels = rng.permutation(n) + 1
+    out = np.zeros(n, np.int32)
+    for c in set(core.tolist()):
+        on = [i for i in range(n) if core[i] == c]
+        by_cpu = sorted(on, key=lambda i: (-int(prio[i]), i))
+        for i, lv in zip(by_cpu, sorted((int(levels[j]) for j in on), reverse=True)):
+            out[i] = lv
+    return out
+
+
+def test_given_priorities_batch_matches_single_calls(oracle):
+    """oracle_gprio_rta_batch is the per-taskset analysis of Sec. 5.4 applied to every taskset of a batch:
+    its indexing of the per-task, per-segment and priority arrays, its outputs and its error reporting are
+    checked against single calls on the slices."""
+    from paper_2406_05221_amd import taskgen
+    rng = np.random.default_rng(11)
+    N = 48
+    batch = taskgen.generate(N, n_cores=3, tasks_per_core=3, max_gseg=3, util=(0.1, 0.5), eta=(0, 3),
+                             share=(0.1, 0.5), period=(5_000, 200_000), overhead=(0, 300), slice_us=1024,
+                             seed=5, stream=41)
+    gprio = np.stack([admissible_levels(rng, batch["prio"][s], batch["core"][s]) for s in range(N)])
+    assert (gprio != batch["prio"]).any(axis=1).sum() > N // 2  # orders that differ from the CPU order
+    for wait in (BUSY, SUSPEND):
+        resp, sched = oracle.gprio_rta_batch(batch, gprio, wait)
+        assert resp.shape == (N, 9) and sched.shape == (N,)
+        assert 0 < sched.sum() < N  # both verdicts occur
+        for s in range(N):
+            r1, s1, _ = oracle.gprio_rta_taskset(
+                batch["cpu_us"][s], batch["period_us"][s], batch["deadline_us"][s], batch["prio"][s],
+                batch["core"][s], batch["n_gseg"][s], batch["gm_us"][s], batch["ge_us"][s], gprio[s],
+                eps_us=batch["eps_us"][s], wait_mode=wait)
+            assert (r1 == resp[s]).all() and s1 == sched[s], s
+
+
+def test_given_priorities_batch_reports_the_first_bad_taskset(oracle):
+    from paper_2406_05221_amd import taskgen
+    rng = np.random.default_rng(12)
+    N = 40
+    batch = taskgen.generate(N, n_cores=2, tasks_per_core=3, max_gseg=2, util=(0.1, 0.4), eta=(1, 2),
+                             share=(0.1, 0.5), period=(5_000, 200_000), overhead=(0, 100), slice_us=1024,
+                             seed=6, stream=42)
+    gprio = np.stack([admissible_levels(rng, batch["prio"][s], batch["core"][s]) for s in range(N)])
+    oracle.gprio_rta_batch(batch, gprio, SUSPEND)
+    # a period of zero: task-model violation, smallest index reported
+    bad = {k: v.copy() for k, v in batch.items()}
+    bad["period_us"][29, 4] = 0
+    bad["period_us"][17, 1] = 0
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.gprio_rta_batch(bad, gprio, SUSPEND)
+    assert e.value.code == oracle.ETASK and e.value.first_bad == 17
+    # two tasks of one core in the opposite order on the GPU (Sec. 4.3 forbids it)
+    g2 = gprio.copy()
+    for s in (33, 21):
+        on0 = [i for i in range(6) if batch["core"][s, i] == 0]
+        a, b = on0[0], on0[1]
+        g2[s, a], g2[s, b] = g2[s, b], g2[s, a]
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.gprio_rta_batch(batch, g2, BUSY)
+    assert e.value.code == oracle.EORDER and e.value.first_bad == 21
+    # the violation with the smaller index wins, whatever its kind
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.gprio_rta_batch(bad, g2, BUSY)
+    assert e.value.code == oracle.ETASK and e.value.first_bad == 17
+
+
 # ---- concrete schedules under separate GPU priorities -------------------------------------------
 @pytest.mark.parametrize("wait", [BUSY, SUSPEND])
 def test_simulated_response_never_exceeds_bound_under_separate_priorities(oracle, wait):

@@ -83,6 +83,10 @@ MUTANTS = {
                                          "      std::vector<char> higher_g(n_tasks, 1);"),
     "continue_after_miss_takes_the_period": ("      tau[k].R = tau[k].D;\n", "      tau[k].R = tau[k].T;\n"),
     "continue_after_miss_takes_zero": ("      tau[k].R = tau[k].D;\n", "      tau[k].R = 0;\n"),
+    "given_priorities_batch_wrong_segment_stride": (
+        "ge_us ? ge_us + so : nullptr, gprio + to,", "ge_us ? ge_us + to : nullptr, gprio + to,"),
+    "given_priorities_batch_wrong_priority_stride": (
+        "ge_us ? ge_us + so : nullptr, gprio + to,", "ge_us ? ge_us + so : nullptr, gprio + s,"),
     "stops_one_iteration_early": ("      } else if (next == R) {\n        break;",
                                   "      } else if (next == R || true) {\n        break;"),
 }
@@ -117,6 +121,7 @@ PINS = [
     lambda o: [gprio_tests.test_search_finds_an_order_iff_one_exists(o, w) for w in (0, 1)],
     lambda o: [gprio_tests.test_simulated_response_never_exceeds_bound_under_separate_priorities(o, w)
                for w in (0, 1)],
+    gprio_tests.test_given_priorities_batch_matches_single_calls,
 ]
 
 
@@ -126,6 +131,7 @@ def mutant_module(oracle, lib):
     m.rta_taskset = lambda *a, **kw: oracle.rta_taskset(*a, lib=lib, **kw)
     m.gprio_rta_taskset = lambda *a, **kw: oracle.gprio_rta_taskset(*a, lib=lib, **kw)
     m.gprio_assign_taskset = lambda *a, **kw: oracle.gprio_assign_taskset(*a, lib=lib, **kw)
+    m.gprio_rta_batch = lambda *a, **kw: oracle.gprio_rta_batch(*a, lib=lib, **kw)
     return m
 
 
@@ -144,7 +150,7 @@ def test_mutant_is_rejected_by_some_pin(oracle, tmp_path, name):
     for k, pin in enumerate(PINS):
         try:
             pin(m)
-        except AssertionError:
+        except (AssertionError, oracle.OracleError):  # a wrong value, or an error where none is due
             killed_by = k
             break
     assert killed_by is not None, f"no pin notices the planted mistake '{name}'"
