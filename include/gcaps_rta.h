@@ -82,7 +82,11 @@ enum {
   GCAPS_ETASK = -2,   /* a taskset violates the task model: T = 0, D = 0, D > T, L = 0, eta^g > S
                          (gcaps_gprio_rta_batch: or its GPU priorities disagree with prio on a core) */
   GCAPS_ENOMEM = -3,  /* host or device allocation failed */
-  GCAPS_EDEVICE = -4  /* a HIP call failed (no device, launch failure, ...) */
+  GCAPS_EDEVICE = -4, /* a HIP call failed (no device, launch failure, ...) */
+  GCAPS_ESIZE = -5    /* the call needs more device scratch than it may take now: a call that the stream is
+                         recording into a HIP graph and that is larger than every direct call made before it
+                         (nothing is freed or allocated; make a direct call of these sizes first), or a batch
+                         beyond the limits of gcaps_rta_batch_device_static */
 };
 
 /* response-time sentinels in out_resp */
@@ -130,12 +134,30 @@ int gcaps_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wa
  * Outputs of an invalid taskset are undefined, all others are complete.
  * The launches of a call may be recorded into a HIP graph (stream capture) once a direct call with
  * the same sizes has been made on the context: that call makes the device allocations, a recorded
- * one makes none.  A recorded call depends on no earlier call and can be replayed any number of
- * times, with direct calls in between.  The same holds for the other device-resident entry points
+ * one makes none (GCAPS_ESIZE when it would have to).  A direct call that needs more scratch than any before
+ * it frees and reallocates the context's buffers: graphs recorded earlier on this context then point
+ * to freed memory and must be recorded again.  A recorded call depends on no earlier call and can be
+ * replayed any number of times, with direct calls in between.  The same holds for the other device-resident entry points
  * (gcaps_gprio_assign_batch_device, gcaps_gprio_rta_batch_device, gcaps_simulate_batch_device).
  */
 int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
                            int64_t *d_out_resp, uint8_t *d_out_sched);
+
+/*
+ * gcaps_rta_batch_device for callers that cannot allocate device memory when they call: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * launches, same results; the scratch of the launches (per-call status words, the hand-over lists
+ * between the launches, the columns of the 64-bit kernel: about 14 MiB) is a fixed array that
+ * every GPU the library runs on holds until the process ends, so the call allocates and frees
+ * nothing, whatever was called before it on the context.
+ * Limits: n_tasksets <= 65536 and n_tasks <= 32, else GCAPS_ESIZE (nothing is queued).
+ * The array is shared by every call of this function on one GPU, from any context: calls that
+ * overlap in time on one GPU race; calls queued on one stream, or otherwise ordered, do not.  The
+ * words that must start at zero are cleared by a kernel at the head of each call.  gcaps_status
+ * and gcaps_last_wide_count report on it like on gcaps_rta_batch_device.
+ */
+int gcaps_rta_batch_device_static(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                                  int64_t *d_out_resp, uint8_t *d_out_sched);
 
 /*
  * Waits for the context's stream and reports on the most recent device-resident

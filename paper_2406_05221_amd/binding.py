@@ -20,14 +20,14 @@ _lib = ctypes.CDLL(LIB_PATH)
 
 GCAPS_POLICY_GCAPS, GCAPS_POLICY_RR, GCAPS_POLICY_BOTH = 1, 2, 3
 GCAPS_WAIT_BUSY, GCAPS_WAIT_SUSPEND = 0, 1
-GCAPS_OK, GCAPS_EINVAL, GCAPS_ETASK, GCAPS_ENOMEM, GCAPS_EDEVICE = 0, -1, -2, -3, -4
+GCAPS_OK, GCAPS_EINVAL, GCAPS_ETASK, GCAPS_ENOMEM, GCAPS_EDEVICE, GCAPS_ESIZE = 0, -1, -2, -3, -4, -5
 GCAPS_RESP_MISS, GCAPS_RESP_NOT_ANALYSED = -1, -2
 
 EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_device", "gcaps_status",
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
            "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
-           "gcaps_last_sim_steps", "gcaps_taskgen_device"]
+           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -47,6 +47,8 @@ _lib.gcaps_rta_batch.restype = _int
 _lib.gcaps_rta_batch.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p, ctypes.POINTER(_u32)]
 _lib.gcaps_rta_batch_device.restype = _int
 _lib.gcaps_rta_batch_device.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p]
+_lib.gcaps_rta_batch_device_static.restype = _int
+_lib.gcaps_rta_batch_device_static.argtypes = [_p, ctypes.POINTER(gcaps_batch), _int, _int, _p, _p]
 _lib.gcaps_status.restype = _int
 _lib.gcaps_status.argtypes = [_p, ctypes.POINTER(_u32)]
 _lib.gcaps_last_wide_count.restype = _int
@@ -156,10 +158,11 @@ def to_device(batch, device="cuda:0"):
     return out
 
 
-def gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched):
+def gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched, static=False):
     """Device entry point.  dbatch: dict of torch device tensors with the batch layout;
     d_resp: int64 [npol, N, n], d_sched: uint8 [npol, N] device tensors.  Queues the work
-    on the context's stream and returns; call ``gcaps_status`` to wait and check."""
+    on the context's stream and returns; call ``gcaps_status`` to wait and check.
+    static: call ``gcaps_rta_batch_device_static`` (no device allocation, bounded sizes)."""
     N, n = dbatch["cpu_us"].shape
     S = dbatch["gm_us"].shape[2] if dbatch["gm_us"].dim() == 3 else 0
     b = gcaps_batch(n_tasksets=int(N), n_tasks=int(n), max_gseg=int(S))
@@ -170,9 +173,15 @@ def gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched):
     P = npol(policy)
     assert d_resp.is_cuda and d_resp.is_contiguous() and d_resp.numel() == P * N * n and d_resp.element_size() == 8
     assert d_sched.is_cuda and d_sched.is_contiguous() and d_sched.numel() == P * N and d_sched.element_size() == 1
-    rc = _lib.gcaps_rta_batch_device(ctx, ctypes.byref(b), policy, wait_mode, d_resp.data_ptr(), d_sched.data_ptr())
+    fn = _lib.gcaps_rta_batch_device_static if static else _lib.gcaps_rta_batch_device
+    rc = fn(ctx, ctypes.byref(b), policy, wait_mode, d_resp.data_ptr(), d_sched.data_ptr())
     if rc != GCAPS_OK:
         raise GcapsError(rc)
+
+
+def gcaps_rta_batch_device_static(ctx, dbatch, policy, wait_mode, d_resp, d_sched):
+    """``gcaps_rta_batch_device`` in the library's fixed scratch array: allocates nothing."""
+    gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched, static=True)
 
 
 def gcaps_status(ctx):

@@ -9,7 +9,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <mutex>
 #include <new>
+#include <utility>
 #include <type_traits>
 
 #include "gcaps_rta.h"
@@ -31,9 +33,13 @@ typedef unsigned long long u64;
 struct DeviceBuffer {
   void *ptr = nullptr;
   size_t bytes = 0;
-  /* grow-only: keeps the allocation when it is already large enough */
-  int reserve(size_t want) {
+  bool fixed = false; /* a slice of memory owned by someone else: never freed, never grown */
+  /* grow-only: keeps the allocation when it is already large enough.  may_grow = false (the stream is
+   * recording into a HIP graph, or the buffer is fixed): a larger request is refused and the
+   * allocation is left as it is. */
+  int reserve(size_t want, bool may_grow = true) {
     if (want <= bytes) return GCAPS_OK;
+    if (fixed || !may_grow) return GCAPS_ESIZE;
     if (ptr) {
       if (hipFree(ptr) != hipSuccess) return GCAPS_EDEVICE;
       ptr = nullptr;
@@ -48,11 +54,68 @@ struct DeviceBuffer {
     return GCAPS_OK;
   }
   void release() {
-    if (ptr) (void)hipFree(ptr);
+    if (ptr && !fixed) (void)hipFree(ptr);
     ptr = nullptr;
     bytes = 0;
   }
 };
+
+/* the device scratch of the analysis launches */
+struct Pool {
+  DeviceBuffer status;       /* three blocks of fast::kStatusWords words: two used by alternate calls, the
+                                third by calls that must not depend on their neighbours (recorded into a
+                                HIP graph, or running in the static scratch) */
+  DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
+  DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
+  DeviceBuffer deep_sorted;  /* the same list, contiguous and ordered (binning) */
+  DeviceBuffer deep_aux;     /* bucket and position inside the bucket of every list entry (binning) */
+  DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
+  void release() {
+    status.release();
+    wide_list.release();
+    deep_list.release();
+    deep_sorted.release();
+    deep_aux.release();
+    wide_scratch.release();
+  }
+};
+
+/*
+ * Scratch of gcaps_rta_batch_device_static: one array per GPU that the library is loaded on,
+ * held until the process ends.  Host code never uses the array's name as an address: the
+ * address on a device is asked for once per device (scratch_on_device) and kept.
+ */
+constexpr size_t kStaticMaxTasksets = 65536; /* keep in step with include/gcaps_rta.h */
+constexpr size_t kStaticMaxTasks = 32;
+constexpr size_t kStaticWideSlots = 8192; /* lanes of the 64-bit kernel in a static call */
+constexpr size_t kStaticRegionCap = ((kStaticMaxTasksets / 16 + 63) / 64) * 64;
+constexpr size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+constexpr size_t kStaticStatusBytes = up256(3 * 448 * sizeof(unsigned));
+constexpr size_t kStaticListBytes = up256(kStaticMaxTasksets * sizeof(unsigned));
+constexpr size_t kStaticDeepBytes = up256(kStaticRegionCap * 64 * sizeof(unsigned));
+constexpr size_t kStaticColumnBytes = up256(kStaticWideSlots * kStaticMaxTasks * (4 * 4 + 3 * 8));
+constexpr size_t kStaticScratchBytes =
+    kStaticStatusBytes + 2 * kStaticListBytes + 3 * kStaticDeepBytes + kStaticColumnBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_of_device[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+/* address of `scratch` on device `dev`, which must be the current device; null on failure */
+void *scratch_on_device(int dev) {
+  if (dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_of_device[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_of_device[dev] = p;
+  }
+  return g_scratch_of_device[dev];
+}
 
 int npol(int policy) { return ((policy & 1) ? 1 : 0) + ((policy & 2) ? 1 : 0); }
 
@@ -74,20 +137,17 @@ struct gcaps_ctx {
   bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
   u32 last_n_tasksets = 0;
   int lds_limit = 65536;     /* dynamic LDS a workgroup may ask for */
-  DeviceBuffer status;       /* three blocks of fast::kStatusWords words: two used by alternate calls, the
-                                third by calls recorded into a HIP graph */
+  Pool pool;                 /* device scratch of the analysis launches (grows on demand) */
+  Pool static_pool;          /* the same buffers as fixed slices of the static scratch array */
+  bool static_call = false;  /* the current call runs in the static scratch: no allocation */
+  u32 *last_status = nullptr; /* status block of the most recent call */
   u32 status_parity = 0;     /* block of the most recent call that ran directly */
   u32 status_block = 0;      /* block of the current (most recent) call */
   bool next_prepared = false; /* the other block has been made ready by the last kernel of that call */
   u32 *next_status = nullptr; /* what the last kernel of the current chunk is to prepare, or null */
   bool capturing = false;     /* the stream is recording the current call into a HIP graph */
-  DeviceBuffer wide_list;    /* taskset indices handed to the 64-bit kernel */
-  DeviceBuffer deep_list;    /* taskset indices alive after the first fast launch */
-  DeviceBuffer deep_sorted;  /* the same list, contiguous and ordered (binning) */
-  DeviceBuffer deep_aux;     /* bucket and position inside the bucket of every list entry (binning) */
   u32 region_cap = 0;        /* slots per region of deep_list in the current chunk */
   size_t lds_total = 65536;  /* LDS of one CU */
-  DeviceBuffer wide_scratch; /* per-lane columns of the wide kernel */
   DeviceBuffer staging_in, staging_out; /* device copies for the host entry point */
   u32 *host_status = nullptr; /* pinned */
 };
@@ -95,7 +155,7 @@ struct gcaps_ctx {
 namespace {
 
 u32 *status_of(const gcaps_ctx *ctx) {
-  return (u32 *)ctx->status.ptr + (size_t)ctx->status_block * fast::kStatusWords;
+  return (u32 *)ctx->pool.status.ptr + (size_t)ctx->status_block * fast::kStatusWords;
 }
 
 struct DeviceGuard {
@@ -126,6 +186,7 @@ int check_batch(const gcaps_batch *b, int policy, int wait_mode, const void *out
  * its scratch columns stay modest */
 u32 wide_slots(const gcaps_ctx *ctx, u32 n_tasksets) {
   u32 cap = (u32)ctx->n_cu * 8u * 256u;
+  if (ctx->static_call) cap = (u32)kStaticWideSlots; /* the kernel's lanes stride over the list */
   u32 want = (n_tasksets + 255u) / 256u * 256u;
   return want < cap ? want : cap;
 }
@@ -134,9 +195,9 @@ u32 wide_slots(const gcaps_ctx *ctx, u32 n_tasksets) {
 int wide_columns(gcaps_ctx *ctx, u32 n_tasks, u32 slots, wide::Scratch *ws) {
   const size_t col = (size_t)slots * n_tasks;
   const size_t bytes = col * (4 * sizeof(u32) + 3 * sizeof(u64));
-  int rc = ctx->wide_scratch.reserve(bytes);
+  int rc = ctx->pool.wide_scratch.reserve(bytes, !ctx->capturing);
   if (rc != GCAPS_OK) return rc;
-  char *base = (char *)ctx->wide_scratch.ptr;
+  char *base = (char *)ctx->pool.wide_scratch.ptr;
   ws->CGm = (u64 *)base;
   ws->Ge = ws->CGm + col;
   ws->K = ws->Ge + col;
@@ -185,7 +246,7 @@ __global__ void reset_status_kernel(u32 *status, int first_chunk) {
 /* Status words at the start of a chunk.  The first chunk of a call finds its block prepared by the
  * last kernel of the previous call (see wide::prepare_next_call); otherwise a small kernel does it. */
 int begin_chunk(gcaps_ctx *ctx, bool first_chunk) {
-  if (first_chunk && ctx->next_prepared && !ctx->capturing) {
+  if (first_chunk && ctx->next_prepared && !ctx->capturing && !ctx->static_call) {
     ctx->next_prepared = false;
     return GCAPS_OK;
   }
@@ -198,11 +259,11 @@ int begin_chunk(gcaps_ctx *ctx, bool first_chunk) {
 fast::ListSpec deep_list_spec(const gcaps_ctx *ctx, bool sorted) {
   u32 *status = status_of(ctx);
   if (sorted)
-    return fast::ListSpec{(u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u, nullptr, nullptr, nullptr};
-  fast::ListSpec dl{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap,
+    return fast::ListSpec{(u32 *)ctx->pool.deep_sorted.ptr, status + fast::ST_DEEP_TOTAL, 1u, 0u, nullptr, nullptr, nullptr};
+  fast::ListSpec dl{(u32 *)ctx->pool.deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions, ctx->region_cap,
                     nullptr, nullptr, nullptr};
   if (ctx->binning) {
-    dl.keys = (u32 *)ctx->deep_aux.ptr;
+    dl.keys = (u32 *)ctx->pool.deep_aux.ptr;
     dl.positions = dl.keys + (size_t)ctx->region_cap * fast::kListRegions;
     dl.hist = status + fast::ST_ORDER_HIST;
   }
@@ -216,7 +277,7 @@ int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mo
   fast::ListSpec dl = deep_list_spec(ctx, false);
   hipLaunchKernelGGL((fast::rta_fast_kernel<TS, NP>), dim3(blocks), dim3(64), lds, ctx->stream, *b,
                      policy, wait_mode, (long long *)d_resp, d_sched, status_of(ctx),
-                     (u32 *)ctx->wide_list.ptr, dl, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                     (u32 *)ctx->pool.wide_list.ptr, dl, kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -225,11 +286,11 @@ int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
   if (wait_mode == GCAPS_WAIT_BUSY)
     hipLaunchKernelGGL(fast::rta_screen_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr,
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr,
                        deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   else
     hipLaunchKernelGGL(fast::rta_screen_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr,
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr,
                        deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
@@ -271,7 +332,7 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
   fast::ListSpec dl = deep_list_spec(ctx, ctx->binning != 0 && !CONT);
   if (CONT) dl = fast::ListSpec{nullptr, nullptr, 1u, N, nullptr, nullptr, nullptr}; /* every taskset */
   hipLaunchKernelGGL((fast::rta_deep_kernel<BUSY, Q, CONT>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                     (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->wide_list.ptr, dl, kr,
+                     (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr, dl, kr,
                      ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
@@ -312,13 +373,13 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   if (ctx->cont) /* the full-depth launch alone */
     ctx->wide_only = n > fast::kMaxTasks || fast::deep_lds_bytes(n, ctx->deep_lanes) > (size_t)ctx->lds_limit;
   if (ctx->wide_only) return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, nullptr, nullptr, N);
-  int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
+  int rc = ctx->pool.wide_list.reserve((size_t)N * sizeof(u32), !ctx->capturing);
   /* tiles of the first launch go to the list regions round-robin: a region never overflows */
   const u32 producer_tiles = (N + 15u) / 16u; /* the narrowest tile width */
   ctx->region_cap = ((producer_tiles + fast::kListRegions - 1) / fast::kListRegions) * 64u;
-  if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32));
+  if (rc == GCAPS_OK) rc = ctx->pool.deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32), !ctx->capturing);
   if (rc == GCAPS_OK && ctx->binning)
-    rc = ctx->deep_aux.reserve((size_t)ctx->region_cap * fast::kListRegions * 2 * sizeof(u32));
+    rc = ctx->pool.deep_aux.reserve((size_t)ctx->region_cap * fast::kListRegions * 2 * sizeof(u32), !ctx->capturing);
   if (rc != GCAPS_OK) return rc;
 
   if (ctx->cont) {
@@ -326,7 +387,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
     rc = launch_deep(ctx, b, policy, wait_mode, d_resp, d_sched, 0u);
     if (rc != GCAPS_OK) return rc;
     const u32 *count = (const u32 *)status_of(ctx) + fast::ST_WIDE_COUNT;
-    return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count,
+    return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->pool.wide_list.ptr, count,
                        N < 65536u ? N : 65536u);
   }
 
@@ -340,12 +401,12 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   /* second launch: the tasksets still alive, in full; persistent workgroups walk the list */
   if (kr < n && ctx->binning) {
     /* the list ordered by the bucket that the first launch gave every entry */
-    rc = ctx->deep_sorted.reserve((size_t)N * sizeof(u32));
+    rc = ctx->pool.deep_sorted.reserve((size_t)N * sizeof(u32), !ctx->capturing);
     if (rc != GCAPS_OK) return rc;
     u32 *status = status_of(ctx);
     hipLaunchKernelGGL(bin::order_kernel, dim3(fast::kListRegions), dim3(256), 0, ctx->stream,
                        deep_list_spec(ctx, false), (const u32 *)(status + fast::ST_ORDER_HIST),
-                       (u32 *)ctx->deep_sorted.ptr, status + fast::ST_DEEP_TOTAL);
+                       (u32 *)ctx->pool.deep_sorted.ptr, status + fast::ST_DEEP_TOTAL);
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
   }
   if (kr < n) {
@@ -355,7 +416,7 @@ int run_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, i
   /* whatever the fast launches handed over is redone in 64 bit; usually nothing */
   const u32 *count = (const u32 *)status_of(ctx) + fast::ST_WIDE_COUNT;
   const u32 items = N < 65536u ? N : 65536u;
-  return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->wide_list.ptr, count, items);
+  return launch_wide(ctx, b, policy, wait_mode, d_resp, d_sched, (const u32 *)ctx->pool.wide_list.ptr, count, items);
 }
 
 /* Splits a call into chunks of tasksets small enough for the kernels' 32-bit byte offsets:
@@ -382,17 +443,21 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
     capture = hipStreamCaptureStatusNone;
   }
   ctx->capturing = capture != hipStreamCaptureStatusNone;
-  if (ctx->capturing) {
+  /* a call in the static scratch is as self-contained as a recorded one: a block of status words of
+   * its own, reset first, nothing prepared for a later call */
+  const bool isolated = ctx->capturing || ctx->static_call;
+  if (isolated) {
     ctx->status_block = 2u;
   } else {
     ctx->status_parity ^= 1u;
     ctx->status_block = ctx->status_parity;
   }
+  ctx->last_status = status_of(ctx);
   bool prepared = false;
   for (u64 c0 = 0; c0 < N; c0 += chunk) {
     const bool last_chunk = c0 + chunk >= N;
-    ctx->next_status = (last_chunk && !ctx->capturing)
-                           ? (u32 *)ctx->status.ptr + (size_t)(ctx->status_parity ^ 1u) * fast::kStatusWords
+    ctx->next_status = (last_chunk && !isolated)
+                           ? (u32 *)ctx->pool.status.ptr + (size_t)(ctx->status_parity ^ 1u) * fast::kStatusWords
                            : nullptr;
     gcaps_batch sub = *b;
     const u64 cn = N - c0 < chunk ? N - c0 : chunk;
@@ -413,12 +478,12 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
     const int rc = run(&sub, c0);
     ctx->next_status = nullptr;
     if (rc != GCAPS_OK) {
-      if (!ctx->capturing) ctx->next_prepared = false; /* the next call resets its block itself */
+      if (!isolated) ctx->next_prepared = false; /* the next call resets its block itself */
       return rc;
     }
     prepared = last_chunk;
   }
-  if (!ctx->capturing) ctx->next_prepared = prepared; /* a recorded call changes nothing for the others */
+  if (!isolated) ctx->next_prepared = prepared; /* a recorded call changes nothing for the others */
   return GCAPS_OK;
 }
 
@@ -443,15 +508,15 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
   const u32 *d_list = nullptr, *d_count = nullptr;
   u32 items = N;
   if (!ctx->wide_only) {
-    int rc = ctx->wide_list.reserve((size_t)N * sizeof(u32));
+    int rc = ctx->pool.wide_list.reserve((size_t)N * sizeof(u32), !ctx->capturing);
     /* tiles of the first launch go to the list regions round-robin: a region never overflows */
     const u32 producer_tiles = (N + 63u) / 64u;
     ctx->region_cap = ((producer_tiles + fast::kListRegions - 1) / fast::kListRegions) * 64u;
-    if (rc == GCAPS_OK) rc = ctx->deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32));
+    if (rc == GCAPS_OK) rc = ctx->pool.deep_list.reserve((size_t)ctx->region_cap * fast::kListRegions * sizeof(u32), !ctx->capturing);
     if (rc != GCAPS_OK) return rc;
-    const fast::ListSpec dl{(u32 *)ctx->deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions,
+    const fast::ListSpec dl{(u32 *)ctx->pool.deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions,
                             ctx->region_cap, nullptr, nullptr, nullptr};
-    u32 *wl = (u32 *)ctx->wide_list.ptr;
+    u32 *wl = (u32 *)ctx->pool.wide_list.ptr;
     /* first launch: every taskset; settles what needs no search and lists the rest */
     hipLaunchKernelGGL(gprio::gprio_screen_kernel, dim3(producer_tiles), dim3(64), 0, ctx->stream, *b, d_skip,
                        (int *)d_gprio, (long long *)d_resp, d_sched, status, wl, dl, ctx->ts_offset);
@@ -665,7 +730,29 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   if (rc == GCAPS_OK && hipGetDeviceProperties(&prop, device_id) != hipSuccess) rc = GCAPS_EDEVICE;
   if (rc == GCAPS_OK) {
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    rc = ctx->status.reserve(3 * fast::kStatusWords * sizeof(u32));
+    rc = ctx->pool.status.reserve(3 * fast::kStatusWords * sizeof(u32));
+    ctx->last_status = (u32 *)ctx->pool.status.ptr;
+  }
+  if (rc == GCAPS_OK) {
+    /* the static scratch of this device, cut into the buffers of a pool */
+    static_assert(kStaticStatusBytes >= 3 * fast::kStatusWords * sizeof(u32), "status blocks");
+    char *base = (char *)scratch_on_device(device_id);
+    if (!base) rc = GCAPS_EDEVICE;
+    auto slice = [&](DeviceBuffer &buf, size_t bytes) {
+      buf.ptr = base;
+      buf.bytes = bytes;
+      buf.fixed = true;
+      base += bytes;
+    };
+    if (rc == GCAPS_OK) {
+      Pool &sp = ctx->static_pool;
+      slice(sp.status, kStaticStatusBytes);
+      slice(sp.wide_list, kStaticListBytes);
+      slice(sp.deep_sorted, kStaticListBytes);
+      slice(sp.deep_list, kStaticDeepBytes);
+      slice(sp.deep_aux, 2 * kStaticDeepBytes);
+      slice(sp.wide_scratch, kStaticColumnBytes);
+    }
   }
   if (rc == GCAPS_OK) {
     /* the fast kernel's tiles live in dynamic LDS: raise the per-workgroup limit to what the CU has */
@@ -693,7 +780,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     rc = GCAPS_ENOMEM;
   if (rc != GCAPS_OK) {
     (void)hipGetLastError();
-    ctx->status.release();
+    ctx->pool.release();
     delete ctx;
     return rc;
   }
@@ -705,12 +792,7 @@ extern "C" void gcaps_destroy(gcaps_ctx *ctx) {
   if (!ctx) return;
   DeviceGuard guard(ctx->device);
   (void)hipStreamSynchronize(ctx->stream);
-  ctx->status.release();
-  ctx->wide_scratch.release();
-  ctx->wide_list.release();
-  ctx->deep_list.release();
-  ctx->deep_sorted.release();
-  ctx->deep_aux.release();
+  ctx->pool.release();
   ctx->staging_in.release();
   ctx->staging_out.release();
   if (ctx->host_status) (void)hipHostFree(ctx->host_status);
@@ -739,11 +821,29 @@ extern "C" int gcaps_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, 
   return run_device(ctx, batch, policy, wait_mode, d_out_resp, d_out_sched);
 }
 
+extern "C" int gcaps_rta_batch_device_static(gcaps_ctx *ctx, const gcaps_batch *batch, int policy, int wait_mode,
+                                             int64_t *d_out_resp, uint8_t *d_out_sched) {
+  if (!ctx) return GCAPS_EINVAL;
+  int rc = check_batch(batch, policy, wait_mode, d_out_resp, d_out_sched);
+  if (rc != GCAPS_OK) return rc;
+  if (batch->n_tasksets > kStaticMaxTasksets || batch->n_tasks > kStaticMaxTasks) return GCAPS_ESIZE;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  /* the launches of gcaps_rta_batch_device with the fixed slices of the static array in place of the
+   * context's own buffers: every reserve() is then a size check */
+  std::swap(ctx->pool, ctx->static_pool);
+  ctx->static_call = true;
+  rc = run_device(ctx, batch, policy, wait_mode, d_out_resp, d_out_sched);
+  ctx->static_call = false;
+  std::swap(ctx->pool, ctx->static_pool);
+  return rc;
+}
+
 extern "C" int gcaps_status(gcaps_ctx *ctx, uint32_t *first_bad_taskset) {
   if (!ctx) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+  if (hipMemcpyAsync(ctx->host_status, ctx->last_status, sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
           hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
@@ -760,7 +860,7 @@ extern "C" int gcaps_last_wide_count(gcaps_ctx *ctx, uint32_t *count) {
   if (!ctx || !count) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), 4 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+  if (hipMemcpyAsync(ctx->host_status, ctx->last_status, 4 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
           hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
@@ -978,7 +1078,7 @@ extern "C" int gcaps_last_sim_steps(gcaps_ctx *ctx, uint64_t *steps) {
   if (!ctx || !steps) return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  if (hipMemcpyAsync(ctx->host_status, status_of(ctx), 8 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
+  if (hipMemcpyAsync(ctx->host_status, ctx->last_status, 8 * sizeof(u32), hipMemcpyDeviceToHost, ctx->stream) !=
           hipSuccess ||
       hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipGetLastError();
@@ -997,6 +1097,9 @@ extern "C" const char *gcaps_strerror(int code) {
              "disagree with the CPU priorities on a core)";
     case GCAPS_ENOMEM: return "host or device allocation failed";
     case GCAPS_EDEVICE: return "a HIP runtime call failed";
+    case GCAPS_ESIZE:
+      return "the call needs more device scratch than it may take (a recorded call larger than every direct call "
+             "before it, or a batch beyond the limits of gcaps_rta_batch_device_static)";
     default: return "unknown gcaps error code";
   }
 }

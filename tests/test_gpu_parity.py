@@ -426,3 +426,65 @@ def test_captured_call_replays(oracle, gpu):
         B.gcaps_status(ctx)
     finally:
         B.gcaps_destroy(ctx)
+
+
+def test_recorded_call_that_would_have_to_allocate_is_refused(oracle, gpu):
+    """A call that the stream is recording into a HIP graph makes no device allocation: when it needs
+    more scratch than every direct call before it, it returns GCAPS_ESIZE and leaves the context's
+    buffers alone (a direct call afterwards works)."""
+    import torch
+    B, _, _ = gpu
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        small, large = relaxed_workload(500, seed=61), relaxed_workload(9_000, seed=62)
+        assert np.array_equal(B.gcaps_rta_batch(ctx, small, BOTH, BUSY)[0], oracle.rta_batch(small, BOTH, BUSY)[0])
+        d = B.to_device(large)
+        N, n = large["cpu_us"].shape
+        d_resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+        d_sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        code = None
+        with torch.cuda.graph(graph, stream=stream):
+            try:
+                B.gcaps_rta_batch_device(ctx, d, BOTH, BUSY, d_resp, d_sched)
+            except B.GcapsError as e:
+                code = e.code
+        assert code == B.GCAPS_ESIZE
+        del graph  # holds at most the status reset; never replayed
+        torch.cuda.synchronize()
+        B.gcaps_rta_batch_device(ctx, d, BOTH, BUSY, d_resp, d_sched)
+        B.gcaps_status(ctx)
+        want_r, want_s, _ = oracle.rta_batch(large, BOTH, BUSY, threads=16)
+        assert np.array_equal(d_resp.cpu().numpy(), want_r) and np.array_equal(d_sched.cpu().numpy(), want_s)
+    finally:
+        B.gcaps_destroy(ctx)
+
+
+def test_argument_and_allocation_failures_leave_the_context_usable(oracle, gpu):
+    """Failures forced from the host: an empty batch (GCAPS_EINVAL) and a batch whose device copy cannot be
+    allocated (GCAPS_ENOMEM: the sizes ask for petabytes; no array is touched before the allocation fails)."""
+    import ctypes
+    B, ctx, _ = gpu
+    good = relaxed_workload(300, seed=71)
+    keep = {name: np.ascontiguousarray(good[name], dtype=dtype) for name, dtype, _ in B._FIELDS}
+    resp = np.empty((2, 300, 20), np.int64)
+    sched = np.empty((2, 300), np.uint8)
+    bad = ctypes.c_uint32(0)
+
+    def call(n_tasksets, n_tasks, max_gseg):
+        b = B.gcaps_batch(n_tasksets=n_tasksets, n_tasks=n_tasks, max_gseg=max_gseg)
+        for name in keep:
+            setattr(b, name, keep[name].ctypes.data)
+        return B._lib.gcaps_rta_batch(ctx, ctypes.byref(b), BOTH, BUSY, resp.ctypes.data, sched.ctypes.data,
+                                      ctypes.byref(bad))
+
+    assert call(0, 20, 3) == B.GCAPS_EINVAL
+    assert call(300, 0, 3) == B.GCAPS_EINVAL
+    assert call(300, 256, 3) == B.GCAPS_EINVAL
+    assert call(0xFFFFFFFF, 255, 255) == B.GCAPS_ENOMEM
+    assert "allocation" in B.gcaps_strerror(B.GCAPS_ENOMEM)
+    assert call(300, 20, 3) == B.GCAPS_OK
+    want_r, want_s, _ = oracle.rta_batch(good, BOTH, BUSY)
+    assert np.array_equal(resp, want_r) and np.array_equal(sched, want_s)
