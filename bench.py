@@ -82,13 +82,15 @@ def main():
                     help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
                          "HBM byte counters collected over this command)")
     ap.add_argument("--print-csrc-hash", action="store_true", help="print the hash of the kernel sources and exit")
-    ap.add_argument("--row", choices=["rta", "gprio", "sim", "stream"], default="rta",
+    ap.add_argument("--row", choices=["rta", "gprio", "sim", "stream", "peak"], default="rta",
                     help="rta (default, the headline): both response-time analyses; gprio: the GPU-segment "
                          "priority assignment (Sec. 4.3 / 5.4) for the tasksets that fail the GCAPS test with "
                          "GPU priority = CPU priority, as in the procedure of Sec. 6.1; sim: schedule simulation "
                          "(observed response times, Sec. 6.2) of lightly loaded tasksets of workload 3's shape; stream: "
                          "every step generates a fresh 1M-taskset batch of the workload on the device and analyses it "
-                         "(workload 5's stream of batches without host-to-device copies)")
+                         "(workload 5's stream of batches without host-to-device copies); peak: the measured 32-bit integer "
+                         "VALU rates of the device (independent chains of one instruction kind at full occupancy), "
+                         "the denominators of the int32_valu figures")
     ap.add_argument("--horizon", type=int, default=1_000_000, help="--row sim: simulated interval (microseconds)")
     ap.add_argument("--search-all", action="store_true", help="--row gprio: search every taskset, skip none")
     ap.add_argument("--continue-after-miss", action="store_true",
@@ -107,6 +109,14 @@ def main():
     from paper_2406_05221_amd import binding as B, taskgen
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.row == "peak":
+        ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
+        rates = B.gcaps_valu_probe(ctx)
+        B.gcaps_destroy(ctx)
+        rates["relative_to_spec"] = {k: v / rates["spec_lane_ops_per_s"] for k, v in rates["lane_ops_per_s"].items()}
+        print(json.dumps(dict(metric="32-bit integer VALU lane-operations/sec by instruction kind, 1 MI355X",
+                              unit="lane-ops/s", n_gpus=1, **rates)))
+        return
     if args.row == "sim":
         return bench_sim(args)
     if args.row == "stream":

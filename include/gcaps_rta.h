@@ -344,6 +344,41 @@ int gcaps_set_binning(gcaps_ctx *ctx, int enable);
  */
 int gcaps_set_continue_after_miss(gcaps_ctx *ctx, int enable);
 
+/*
+ * Measured integer VALU rates of the context's device: the denominator of the fraction of the 32-bit
+ * integer VALU peak that the metric of this library's benchmark names (no passage of the paper: it never
+ * times its analysis).  For each instruction kind a kernel of independent dependency chains of that one
+ * instruction, eight wavefronts per SIMD, is timed with events on the context's stream (the call waits for
+ * the stream, allocates a few KB of device memory for the duration of the call and frees it).
+ *   lane_ops_per_s[k]  lane-operations per second of kind k (a wavefront instruction = 64; multiply-add = 1);
+ *                      GCAPS_PROBE_TERM is the four-instruction sequence of one interference term
+ *                      ceil((R + J) / T) * cost of the fast kernels (add, mul_hi_u24, shift, mad_u24),
+ *                      counted as four lane-operations
+ *   cu_count, clock_khz, wavefront_size, simd_per_cu   as the HIP runtime reports them for the device
+ *   spec_lane_ops_per_s   cu_count * simd_per_cu * 16 lanes * clock: one full-rate 32-bit operation per
+ *                      lane and cycle
+ * Errors: GCAPS_EINVAL, GCAPS_ENOMEM, GCAPS_EDEVICE.
+ */
+enum {
+  GCAPS_PROBE_ADD_U32 = 0,
+  GCAPS_PROBE_MAD_U32_U24 = 1,
+  GCAPS_PROBE_MUL_HI_U32_U24 = 2,
+  GCAPS_PROBE_MUL_LO_U32 = 3,
+  GCAPS_PROBE_MUL_HI_U32 = 4,
+  GCAPS_PROBE_LSHRREV_B32 = 5,
+  GCAPS_PROBE_MIN_U32 = 6,
+  GCAPS_PROBE_TERM = 7,
+  GCAPS_PROBE_CNDMASK_SGPR = 8, /* v_cndmask_b32 selecting by a mask held in a scalar register pair */
+  GCAPS_PROBE_CMP_CNDMASK = 9,  /* v_cmp_lt_u32 + v_cndmask_b32 (a branch-free minimum): two lane-operations */
+  GCAPS_PROBE_KINDS = 10
+};
+typedef struct {
+  int cu_count, clock_khz, wavefront_size, simd_per_cu;
+  double spec_lane_ops_per_s;
+  double lane_ops_per_s[GCAPS_PROBE_KINDS];
+} gcaps_valu_rates;
+int gcaps_valu_probe(gcaps_ctx *ctx, gcaps_valu_rates *out);
+
 /* Static description of an error code. */
 const char *gcaps_strerror(int code);
 

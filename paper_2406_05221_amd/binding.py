@@ -27,7 +27,7 @@ EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
            "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
-           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static"]
+           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static", "gcaps_valu_probe"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -67,6 +67,18 @@ _lib.gcaps_set_continue_after_miss.restype = _int
 _lib.gcaps_set_continue_after_miss.argtypes = [_p, _int]
 _lib.gcaps_strerror.restype = ctypes.c_char_p
 _lib.gcaps_strerror.argtypes = [_int]
+
+PROBE_KINDS = ["add_u32", "mad_u32_u24", "mul_hi_u32_u24", "mul_lo_u32", "mul_hi_u32", "lshrrev_b32", "min_u32",
+               "term", "cndmask_sgpr", "cmp_cndmask"]
+
+
+class gcaps_valu_rates(ctypes.Structure):
+    _fields_ = [("cu_count", _int), ("clock_khz", _int), ("wavefront_size", _int), ("simd_per_cu", _int),
+                ("spec_lane_ops_per_s", ctypes.c_double), ("lane_ops_per_s", ctypes.c_double * len(PROBE_KINDS))]
+
+
+_lib.gcaps_valu_probe.restype = _int
+_lib.gcaps_valu_probe.argtypes = [_p, ctypes.POINTER(gcaps_valu_rates)]
 
 _FIELDS = [("theta_us", np.uint32, 1), ("eps_us", np.uint32, 1), ("slice_us", np.uint32, 1),
            ("cpu_us", np.uint32, 2), ("period_us", np.uint32, 2), ("deadline_us", np.uint32, 2),
@@ -182,6 +194,18 @@ def gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched, stat
 def gcaps_rta_batch_device_static(ctx, dbatch, policy, wait_mode, d_resp, d_sched):
     """``gcaps_rta_batch_device`` in the library's fixed scratch array: allocates nothing."""
     gcaps_rta_batch_device(ctx, dbatch, policy, wait_mode, d_resp, d_sched, static=True)
+
+
+def gcaps_valu_probe(ctx):
+    """Measured integer VALU rates of the device: dict with cu_count, clock_khz, wavefront_size,
+    simd_per_cu, spec_lane_ops_per_s and lane_ops_per_s (by instruction kind)."""
+    r = gcaps_valu_rates()
+    rc = _lib.gcaps_valu_probe(ctx, ctypes.byref(r))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    return dict(cu_count=r.cu_count, clock_khz=r.clock_khz, wavefront_size=r.wavefront_size,
+                simd_per_cu=r.simd_per_cu, spec_lane_ops_per_s=r.spec_lane_ops_per_s,
+                lane_ops_per_s={k: r.lane_ops_per_s[i] for i, k in enumerate(PROBE_KINDS)})
 
 
 def gcaps_status(ctx):

@@ -24,6 +24,7 @@
 #include "gprio_fast.hip.inc"
 #include "sim.hip.inc"
 #include "taskgen_device.hip.inc"
+#include "valu_probe.hip.inc"
 
 namespace {
 
@@ -1085,6 +1086,45 @@ extern "C" int gcaps_last_sim_steps(gcaps_ctx *ctx, uint64_t *steps) {
     return GCAPS_EDEVICE;
   }
   *steps = (uint64_t)ctx->host_status[sim::kStatusSteps] | (uint64_t)ctx->host_status[sim::kStatusSteps + 1] << 32;
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_valu_probe(gcaps_ctx *ctx, gcaps_valu_rates *out) {
+  if (!ctx || !out) return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) return GCAPS_EDEVICE;
+  out->cu_count = prop.multiProcessorCount;
+  out->clock_khz = prop.clockRate;
+  out->wavefront_size = prop.warpSize;
+  out->simd_per_cu = 4; /* CDNA: four SIMDs of 16 lanes per compute unit */
+  out->spec_lane_ops_per_s = (double)out->cu_count * out->simd_per_cu * 16.0 * (double)out->clock_khz * 1e3;
+  const u32 blocks = (u32)ctx->n_cu * 8u; /* 256 threads each: eight wavefronts per SIMD */
+  DeviceBuffer sink;
+  int rc = sink.reserve((size_t)blocks * sizeof(u32));
+  if (rc != GCAPS_OK) return rc;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+  for (int kind = 0; kind < GCAPS_PROBE_KINDS && ok; ++kind) {
+    double best_ms = 0.0;
+    for (int rep = 0; rep < 4 && ok; ++rep) { /* the first repetition warms up; the fastest of the rest counts */
+      ok = hipEventRecord(e0, ctx->stream) == hipSuccess &&
+           probe::launch_kind(kind, ctx->stream, blocks, (u32 *)sink.ptr) == hipSuccess &&
+           hipEventRecord(e1, ctx->stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+      float ms = 0.0f;
+      ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+      if (ok && rep > 0 && (best_ms == 0.0 || ms < best_ms)) best_ms = ms;
+    }
+    out->lane_ops_per_s[kind] = best_ms > 0.0 ? probe::lane_ops(kind, blocks) / (best_ms * 1e-3) : 0.0;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  sink.release();
+  if (!ok) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
   return GCAPS_OK;
 }
 
