@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libgcaps_rta.so")
+# GCAPS_RTA_LIBRARY: another build of the same sources (e.g. with other tuning macros) instead of the in-tree one
+LIB_PATH = os.environ.get("GCAPS_RTA_LIBRARY") or os.path.join(_PKG, "libgcaps_rta.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "

@@ -19,6 +19,7 @@
 #include "rta_wide.hip.inc"
 #include "rta_fast.hip.inc"
 #include "rta_deep.hip.inc"
+#include "rta_quad.hip.inc"
 #include "rta_bin.hip.inc"
 #include "gprio_wide.hip.inc"
 #include "gprio_fast.hip.inc"
@@ -91,7 +92,7 @@ constexpr size_t kStaticMaxTasks = 32;
 constexpr size_t kStaticWideSlots = 8192; /* lanes of the 64-bit kernel in a static call */
 constexpr size_t kStaticRegionCap = ((kStaticMaxTasksets / 16 + 63) / 64) * 64;
 constexpr size_t up256(size_t x) { return (x + 255) / 256 * 256; }
-constexpr size_t kStaticStatusBytes = up256(3 * 448 * sizeof(unsigned));
+constexpr size_t kStaticStatusBytes = up256(3 * (size_t)fast::kStatusWords * sizeof(unsigned));
 constexpr size_t kStaticListBytes = up256(kStaticMaxTasksets * sizeof(unsigned));
 constexpr size_t kStaticDeepBytes = up256(kStaticRegionCap * 64 * sizeof(unsigned));
 constexpr size_t kStaticColumnBytes = up256(kStaticWideSlots * kStaticMaxTasks * (4 * 4 + 3 * 8));
@@ -133,6 +134,7 @@ struct gcaps_ctx {
                                every lane then takes many tasksets) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
   u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
+  bool legacy_deep = false; /* GCAPS_DEEP_KERNEL=lds: the second launch in its LDS-record form for every shape */
   size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
   u32 ts_offset = 0;                        /* first taskset of the current chunk */
   bool wide_only = false;   /* last call: shape outside the fast kernel, everything went 64-bit */
@@ -285,14 +287,15 @@ int launch_fast_np(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mo
 int launch_screen(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                   uint8_t *d_sched, u32 kr, u32 blocks) {
   const size_t lds = fast::lds_bytes(b->n_tasks, kr, 64, true);
+  const fast::ListSpec dl = deep_list_spec(ctx, false);
   if (wait_mode == GCAPS_WAIT_BUSY)
     hipLaunchKernelGGL(fast::rta_screen_kernel<true>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr,
-                       deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr, dl, kr,
+                       ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   else
     hipLaunchKernelGGL(fast::rta_screen_kernel<false>, dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
-                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr,
-                       deep_list_spec(ctx, false), kr, ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
+                       (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr, dl, kr,
+                       ctx->resp_stride, ctx->sched_stride, ctx->ts_offset);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
@@ -338,6 +341,44 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 
+/* second launch in its register form (rta_quad.hip.inc): four lanes per taskset, n <= 4 * NSMAX */
+template <bool BUSY, int NSMAX>
+int launch_quad(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_resp, uint8_t *d_sched, u32 kr,
+                const fast::ListSpec &dl) {
+  const u32 n = b->n_tasks, N = b->n_tasksets;
+  const size_t lds = fast::quad_lds_bytes(n);
+  /* exactly as many workgroups as are resident at once: a workgroup's first tile is its own index */
+  int per_cu = 0;
+  const void *fn = (const void *)fast::rta_quad_kernel<BUSY, NSMAX>;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
+    (void)hipGetLastError();
+    per_cu = 1;
+  }
+  u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
+  const u32 max_tiles = (N + 15u) / 16u + fast::kListRegions;
+  if (blocks > max_tiles) blocks = max_tiles;
+  hipLaunchKernelGGL((fast::rta_quad_kernel<BUSY, NSMAX>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+                     (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr, dl, kr,
+                     ctx->resp_stride, ctx->sched_stride);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+int launch_quad_any(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
+                    uint8_t *d_sched, u32 kr, const fast::ListSpec &dl) {
+  const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+#define GCAPS_QUAD(NS)                                                                                   \
+  (busy ? launch_quad<true, NS>(ctx, b, policy, d_resp, d_sched, kr, dl)               \
+        : launch_quad<false, NS>(ctx, b, policy, d_resp, d_sched, kr, dl))
+  if (b->n_tasks <= 20) return GCAPS_QUAD(5);
+  if (b->n_tasks <= 24) return GCAPS_QUAD(6);
+  return GCAPS_QUAD(8);
+#undef GCAPS_QUAD
+}
+
+bool quad_applies(const gcaps_ctx *ctx, const gcaps_batch *b) {
+  return !ctx->cont && ctx->deep_lanes == 4 && b->n_tasks <= fast::kQuadMaxTasks && !ctx->legacy_deep;
+}
+
 template <bool CONT>
 int launch_deep_c(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                   uint8_t *d_sched, u32 kr) {
@@ -351,6 +392,8 @@ int launch_deep_c(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
 
 int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr) {
+  if (quad_applies(ctx, b))
+    return launch_quad_any(ctx, b, policy, wait_mode, d_resp, d_sched, kr, deep_list_spec(ctx, ctx->binning != 0));
   return ctx->cont ? launch_deep_c<true>(ctx, b, policy, wait_mode, d_resp, d_sched, kr)
                    : launch_deep_c<false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr);
 }
@@ -721,6 +764,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     const long v = strtol(e, nullptr, 10);
     if (v >= 1 && v <= 255) ctx->screen_tasks = (u32)v;
   }
+  if (const char *e = getenv("GCAPS_DEEP_KERNEL")) ctx->legacy_deep = e[0] == 'l';
   if (const char *e = getenv("GCAPS_DEEP_LANES")) {
     const long v = strtol(e, nullptr, 10);
     if (v == 4 || v == 8) ctx->deep_lanes = (u32)v;
@@ -769,7 +813,10 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_deep_kernel<true, 4, false>, (const void *)fast::rta_deep_kernel<false, 4, false>,
         (const void *)fast::rta_deep_kernel<true, 8, false>, (const void *)fast::rta_deep_kernel<false, 8, false>,
         (const void *)fast::rta_deep_kernel<true, 4, true>, (const void *)fast::rta_deep_kernel<false, 4, true>,
-        (const void *)fast::rta_deep_kernel<true, 8, true>, (const void *)fast::rta_deep_kernel<false, 8, true>};
+        (const void *)fast::rta_deep_kernel<true, 8, true>, (const void *)fast::rta_deep_kernel<false, 8, true>,
+        (const void *)fast::rta_quad_kernel<true, 5>, (const void *)fast::rta_quad_kernel<false, 5>,
+        (const void *)fast::rta_quad_kernel<true, 6>, (const void *)fast::rta_quad_kernel<false, 6>,
+        (const void *)fast::rta_quad_kernel<true, 8>, (const void *)fast::rta_quad_kernel<false, 8>};
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;

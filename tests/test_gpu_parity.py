@@ -231,8 +231,10 @@ def test_chunked_calls(oracle, monkeypatch):
         B.gcaps_destroy(ctx)
 
 
-@pytest.mark.parametrize("screen_tasks,deep_lanes", [(1, 4), (3, 8), (4, 8), (6, 4), (6, 8), (9, 4), (64, 4)])
-def test_launch_split_knobs(oracle, monkeypatch, screen_tasks, deep_lanes):
+@pytest.mark.parametrize("screen_tasks,deep_lanes,deep_kernel", [(1, 4, ""), (3, 8, ""), (4, 8, ""), (6, 4, ""), (6, 8, ""),
+                                                                  (9, 4, ""), (64, 4, ""), (4, 4, "lds"), (2, 4, "lds"),
+                                                                  (7, 4, "lds")])
+def test_launch_split_knobs(oracle, monkeypatch, screen_tasks, deep_lanes, deep_kernel):
     """How many ranks the first launch analyses and how many lanes share a taskset in the second
     are tuning knobs: results are the same for every setting, also where the second launch resumes
     from more ranks than it has lanes per taskset, and where the first launch settles everything."""
@@ -240,6 +242,8 @@ def test_launch_split_knobs(oracle, monkeypatch, screen_tasks, deep_lanes):
     from paper_2406_05221_amd import binding as B
     monkeypatch.setenv("GCAPS_SCREEN_TASKS", str(screen_tasks))
     monkeypatch.setenv("GCAPS_DEEP_LANES", str(deep_lanes))
+    if deep_kernel:
+        monkeypatch.setenv("GCAPS_DEEP_KERNEL", deep_kernel)  # the LDS-record form of the second launch for every shape
     ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
     try:
         compare(oracle, B, ctx, relaxed_workload(3_001, seed=31))
