@@ -342,14 +342,14 @@ int launch_deep_q(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_r
 }
 
 /* second launch in its register form (rta_quad.hip.inc): four lanes per taskset, n <= 4 * NSMAX */
-template <bool BUSY, int NSMAX>
+template <bool BUSY, int NSMAX, int SEGS>
 int launch_quad(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_resp, uint8_t *d_sched, u32 kr,
                 const fast::ListSpec &dl) {
   const u32 n = b->n_tasks, N = b->n_tasksets;
   const size_t lds = fast::quad_lds_bytes(n);
   /* exactly as many workgroups as are resident at once: a workgroup's first tile is its own index */
   int per_cu = 0;
-  const void *fn = (const void *)fast::rta_quad_kernel<BUSY, NSMAX>;
+  const void *fn = (const void *)fast::rta_quad_kernel<BUSY, NSMAX, SEGS>;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
     (void)hipGetLastError();
     per_cu = 1;
@@ -357,7 +357,7 @@ int launch_quad(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_res
   u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
   const u32 max_tiles = (N + 15u) / 16u + fast::kListRegions;
   if (blocks > max_tiles) blocks = max_tiles;
-  hipLaunchKernelGGL((fast::rta_quad_kernel<BUSY, NSMAX>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
+  hipLaunchKernelGGL((fast::rta_quad_kernel<BUSY, NSMAX, SEGS>), dim3(blocks), dim3(64), lds, ctx->stream, *b, policy,
                      (long long *)d_resp, d_sched, status_of(ctx), (u32 *)ctx->pool.wide_list.ptr, dl, kr,
                      ctx->resp_stride, ctx->sched_stride);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
@@ -366,13 +366,18 @@ int launch_quad(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int64_t *d_res
 int launch_quad_any(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                     uint8_t *d_sched, u32 kr, const fast::ListSpec &dl) {
   const bool busy = wait_mode == GCAPS_WAIT_BUSY;
-#define GCAPS_QUAD(NS)                                                                                   \
-  (busy ? launch_quad<true, NS>(ctx, b, policy, d_resp, d_sched, kr, dl)               \
-        : launch_quad<false, NS>(ctx, b, policy, d_resp, d_sched, kr, dl))
+#define GCAPS_QUAD_S(NS, SEGS)                                                  \
+  (busy ? launch_quad<true, NS, SEGS>(ctx, b, policy, d_resp, d_sched, kr, dl) \
+        : launch_quad<false, NS, SEGS>(ctx, b, policy, d_resp, d_sched, kr, dl))
+#define GCAPS_QUAD(NS)                                                                           \
+  (b->max_gseg <= 4 ? GCAPS_QUAD_S(NS, 4)                                                        \
+                    : b->max_gseg <= (u32)fast::kPrefetchSegs ? GCAPS_QUAD_S(NS, fast::kPrefetchSegs) \
+                                                              : GCAPS_QUAD_S(NS, 0))
   if (b->n_tasks <= 20) return GCAPS_QUAD(5);
   if (b->n_tasks <= 24) return GCAPS_QUAD(6);
   return GCAPS_QUAD(8);
 #undef GCAPS_QUAD
+#undef GCAPS_QUAD_S
 }
 
 bool quad_applies(const gcaps_ctx *ctx, const gcaps_batch *b) {
@@ -814,9 +819,13 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_deep_kernel<true, 8, false>, (const void *)fast::rta_deep_kernel<false, 8, false>,
         (const void *)fast::rta_deep_kernel<true, 4, true>, (const void *)fast::rta_deep_kernel<false, 4, true>,
         (const void *)fast::rta_deep_kernel<true, 8, true>, (const void *)fast::rta_deep_kernel<false, 8, true>,
-        (const void *)fast::rta_quad_kernel<true, 5>, (const void *)fast::rta_quad_kernel<false, 5>,
-        (const void *)fast::rta_quad_kernel<true, 6>, (const void *)fast::rta_quad_kernel<false, 6>,
-        (const void *)fast::rta_quad_kernel<true, 8>, (const void *)fast::rta_quad_kernel<false, 8>};
+#define GCAPS_QUAD_KERNELS(NS)                                                                                        \
+  (const void *)fast::rta_quad_kernel<true, NS, 4>, (const void *)fast::rta_quad_kernel<false, NS, 4>,                \
+      (const void *)fast::rta_quad_kernel<true, NS, fast::kPrefetchSegs>,                                             \
+      (const void *)fast::rta_quad_kernel<false, NS, fast::kPrefetchSegs>,                                            \
+      (const void *)fast::rta_quad_kernel<true, NS, 0>, (const void *)fast::rta_quad_kernel<false, NS, 0>
+        GCAPS_QUAD_KERNELS(5), GCAPS_QUAD_KERNELS(6), GCAPS_QUAD_KERNELS(8)};
+#undef GCAPS_QUAD_KERNELS
     bool raised = want > 65536;
     for (size_t k = 0; k < sizeof(kernels) / sizeof(kernels[0]) && raised; ++k)
       raised = hipFuncSetAttribute(kernels[k], hipFuncAttributeMaxDynamicSharedMemorySize, (int)want) == hipSuccess;
