@@ -91,6 +91,9 @@ def main():
                          "(workload 5's stream of batches without host-to-device copies); peak: the measured 32-bit integer "
                          "VALU rates of the device (independent chains of one instruction kind at full occupancy), "
                          "the denominators of the int32_valu figures")
+    ap.add_argument("--recipe", choices=["workload", "table3"], default="workload",
+                    help="--row stream: generate the named workload (default) or the paper's own recipe (Sec. 6.1, "
+                         "Table 3: 12-24 tasks per taskset, grouped by task count on the device)")
     ap.add_argument("--horizon", type=int, default=1_000_000, help="--row sim: simulated interval (microseconds)")
     ap.add_argument("--search-all", action="store_true", help="--row gprio: search every taskset, skip none")
     ap.add_argument("--continue-after-miss", action="store_true",
@@ -336,6 +339,76 @@ def bench_gprio(args, batch, N, cores, per_core, S):
     print(json.dumps(out))
 
 
+def bench_stream_table3(args):
+    """One step = N fresh tasksets of the recipe of Sec. 6.1 / Table 3 generated on the device (counted, grouped
+    by task count, written as one batch per count) and analysed under both policies, self-suspension.  The groups
+    of the last step are copied back and analysed by the oracle."""
+    import numpy as np
+    import torch
+    from paper_2406_05221_amd import binding as B
+
+    N = args.tasksets or 200_000
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    wait = B.GCAPS_WAIT_SUSPEND
+
+    def step(k):
+        groups = B.gcaps_table3_device(ctx, N, seed=0, stream=300, first_index=k * N)
+        outs = {}
+        for n, (idx, d) in groups.items():
+            M = int(idx.numel())
+            outs[n] = (torch.empty((2, M, n), dtype=torch.int64, device="cuda:0"),
+                       torch.empty((2, M), dtype=torch.uint8, device="cuda:0"))
+        torch.cuda.synchronize()
+        for n, (idx, d) in groups.items():
+            B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, *outs[n])
+        B.gcaps_status(ctx)
+        return groups, outs
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        groups, outs = step(args.warmup + k)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    cpu = None
+    alg_bytes = 0
+    for n, (idx, d) in groups.items():
+        S = d["gm_us"].shape[2]
+        inputs = 3 * 4 + n * (4 * 4 + 2 * 1) + n * S * 2 * 4
+        alg_bytes += int(idx.numel()) * (inputs + algorithmic_bytes_per_taskset(n, S, 2))
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = os.cpu_count() or 1
+        host = {n: B.to_host(d) for n, (idx, d) in groups.items()}
+        t0c = time.perf_counter()
+        want = {n: oracle.rta_batch(h, oracle.POLICY_BOTH, wait, threads=threads) for n, h in host.items()}
+        t_all = time.perf_counter() - t0c
+        same = all(bool((outs[n][0].cpu().numpy() == want[n][0]).all() and (outs[n][1].cpu().numpy() == want[n][1]).all())
+                   for n in host)
+        cpu = dict(value=N / t_all, unit="tasksets/s", cores=threads, kind="oracle",
+                   sample=f"the tasksets of the last step ({N}, copied back), analysis only, {threads} std::thread "
+                          f"workers over tasksets", gpu_matches_oracle_on_sample=same)
+    ms = (t1 - t0) * 1e3 / args.steps
+    achieved = alg_bytes / (ms * 1e-3) / 1e9
+    out = dict(metric="tasksets generated on the device and analysed/sec (GCAPS + round-robin), 1 MI355X",
+               value=N * args.steps / (t1 - t0), unit="tasksets/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=ms, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="u32", data="synthetic",
+               config=dict(workload=f"the recipe of Sec. 6.1 / Table 3: {N} tasksets per step, 4 CPUs x 3-6 tasks, 40-60 % "
+                                    f"GPU-using tasks with 1-3 segments, periods 30-500 ms, eps 1 ms, theta 200 us; counted, "
+                                    f"grouped by task count ({len(groups)} batches) and analysed under both policies, "
+                                    f"self-suspension; wall clock with the host's grouping in it",
+                           tasksets=N, wait_mode="suspend", row="stream", recipe="table3"),
+               roofline=dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                             traffic=None, kernel="gen::table3_* + gcaps_rta_batch_device (all launches of one step)",
+                             algorithmic_bytes_per_step=alg_bytes),
+               cpu_baseline=cpu)
+    B.gcaps_destroy(ctx)
+    print(json.dumps(out))
+
+
 def bench_stream(args):
     """One step = one fresh batch of the workload generated on the device (taskset indices continue from
     batch to batch) and analysed under both policies: the stream of batches of workload 5 with no host-to-device
@@ -343,6 +416,9 @@ def bench_stream(args):
     import numpy as np
     import torch
     from paper_2406_05221_amd import binding as B, taskgen
+
+    if args.recipe == "table3":
+        return bench_stream_table3(args)
 
     k = args.workload if args.workload in (1, 2, 3, 4, 5) else 5
     N = args.tasksets or min(taskgen.CONFIG_SIZES[k], 1_000_000)

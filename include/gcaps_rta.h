@@ -291,8 +291,9 @@ int gcaps_simulate_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, const 
  * rate-monotonic priorities over the taskset; tasks i*tasks_per_core .. on core i.  Taskset k of the call uses
  * the random stream (seed, stream, first_index + k): a batch can be generated in pieces and regenerated.
  * The *_fixed members, if not NULL, are DEVICE arrays [n_tasksets] that fix a value per taskset instead of
- * drawing it.  Integer decisions are taken from double-precision values computed with the device's math library;
- * they can differ by one unit from the host generator's in rare elements.
+ * drawing it.  The batch is the host generator's bit for bit: integer random streams, IEEE double operations in
+ * one fixed order without fused multiply-add, and the generator's own logarithm and power routines on both sides.
+ * A CPU-only task (eta^g = 0 drawn) keeps its whole demand u T as CPU time.
  * batch: sizes and DEVICE pointers of the buffers to fill (n_tasks must equal n_cores * tasks_per_core, eta_hi
  * <= max_gseg; n_cseg is ignored); the call queues one kernel on the context's stream and returns.
  * Errors: GCAPS_EINVAL for null pointers or inconsistent ranges, GCAPS_EDEVICE.
@@ -313,6 +314,44 @@ typedef struct {
 } gcaps_taskgen_spec;
 
 int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *spec, const gcaps_batch *batch);
+
+/*
+ * The generation recipe of the schedulability experiments on the device (Sec. 6.1, Table 3): per CPU a number
+ * of tasks drawn from [per_cpu_lo, per_cpu_hi] and a utilisation drawn from [util_lo, util_hi], split over the
+ * tasks by UUniFast; periods uniform in [period_lo, period_hi] (D = T); round(ratio n) tasks, ratio drawn from
+ * [gpu_ratio_lo, gpu_ratio_hi] and the tasks chosen at random, use the GPU with eta^g in [eta_lo, eta_hi]
+ * segments; C + G = u T; G / C drawn from [gc_lo, gc_hi]; G dealt evenly to the segments and each segment split
+ * by G^m / G drawn from [gm_lo, gm_hi] (whole microseconds, G^e >= 1); rate-monotonic priorities; tasks
+ * re-allocated to the CPUs by worst-fit decreasing (by utilisation, ties by index; at most 8 CPUs).  theta,
+ * epsilon and L are constants.  Taskset k of the stream (seed, stream, first_index + k) is the one the host
+ * generator of this package produces for the same parameters, bit for bit.
+ *
+ * Tasksets differ in their number of tasks; a batch holds tasksets of one count:
+ *   gcaps_table3_count_device     writes the task count of tasksets 0 .. n_tasksets-1 to d_n_tasks (DEVICE,
+ *                                 uint32 [n_tasksets]);
+ *   gcaps_table3_generate_device  fills `batch` (sizes and DEVICE pointers as for gcaps_taskgen_device;
+ *                                 max_gseg >= eta_hi): row r is taskset d_index[r] (DEVICE, uint32
+ *                                 [batch->n_tasksets]; NULL: taskset r), which must have batch->n_tasks tasks.
+ *                                 A taskset of another count leaves its row unwritten and makes gcaps_status
+ *                                 report GCAPS_ETASK with the smallest such row.
+ * Both queue one kernel on the context's stream and return.  Errors: GCAPS_EINVAL (null pointers,
+ * inconsistent ranges, more than 8 CPUs, more than 255 tasks), GCAPS_EDEVICE.
+ */
+typedef struct {
+  uint64_t seed, stream, first_index;
+  uint32_t n_cpus, per_cpu_lo, per_cpu_hi;
+  double gpu_ratio_lo, gpu_ratio_hi;
+  double util_lo, util_hi;
+  uint32_t period_lo, period_hi;
+  uint32_t eta_lo, eta_hi;
+  double gc_lo, gc_hi;
+  double gm_lo, gm_hi;
+  uint32_t theta_us, eps_us, slice_us;
+} gcaps_table3_spec;
+
+int gcaps_table3_count_device(gcaps_ctx *ctx, const gcaps_table3_spec *spec, uint32_t n_tasksets, uint32_t *d_n_tasks);
+int gcaps_table3_generate_device(gcaps_ctx *ctx, const gcaps_table3_spec *spec, const uint32_t *d_index,
+                                 const gcaps_batch *batch);
 
 /*
  * Diagnostics of the most recent gcaps_simulate_batch[_device] call (waits for the stream): the number of

@@ -28,7 +28,8 @@ EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
            "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
-           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static", "gcaps_valu_probe"]
+           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static", "gcaps_valu_probe",
+           "gcaps_table3_count_device", "gcaps_table3_generate_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
 
@@ -454,6 +455,72 @@ def gcaps_taskgen_device(ctx, n_tasksets, *, n_cores, tasks_per_core, max_gseg, 
     if keep:
         torch.cuda.synchronize()  # the per-taskset arrays must outlive the kernel that reads them
     return out
+
+
+class gcaps_table3_spec(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("stream", ctypes.c_uint64), ("first_index", ctypes.c_uint64),
+                ("n_cpus", _u32), ("per_cpu_lo", _u32), ("per_cpu_hi", _u32),
+                ("gpu_ratio_lo", ctypes.c_double), ("gpu_ratio_hi", ctypes.c_double),
+                ("util_lo", ctypes.c_double), ("util_hi", ctypes.c_double),
+                ("period_lo", _u32), ("period_hi", _u32), ("eta_lo", _u32), ("eta_hi", _u32),
+                ("gc_lo", ctypes.c_double), ("gc_hi", ctypes.c_double), ("gm_lo", ctypes.c_double),
+                ("gm_hi", ctypes.c_double), ("theta_us", _u32), ("eps_us", _u32), ("slice_us", _u32)]
+
+
+_lib.gcaps_table3_count_device.restype = _int
+_lib.gcaps_table3_count_device.argtypes = [_p, ctypes.POINTER(gcaps_table3_spec), _u32, _p]
+_lib.gcaps_table3_generate_device.restype = _int
+_lib.gcaps_table3_generate_device.argtypes = [_p, ctypes.POINTER(gcaps_table3_spec), _p, ctypes.POINTER(gcaps_batch)]
+
+
+def gcaps_table3_device(ctx, n_tasksets, *, seed=0, stream=300, first_index=0, device="cuda:0", **overrides):
+    """The recipe of Sec. 6.1 / Table 3 generated on the device, with the parameters of ``taskgen.table3`` (any
+    of ``taskgen.TABLE3`` can be overridden by keyword; best-effort tasks are not generated here).  Returns
+    {n: (indices, batch)} like ``taskgen.table3``: one device batch per task count n, `indices` (int64 device
+    tensor) saying which tasksets of the stream its rows are.  The tasksets are the host generator's, bit for bit.
+    Tensor bookkeeping (grouping by count) is done with torch on the device; one small copy of the distinct counts
+    comes back to the host."""
+    import torch
+    from . import taskgen
+    q = dict(taskgen.TABLE3)
+    unknown = set(overrides) - set(q)
+    if unknown:
+        raise ValueError(f"unknown Table 3 parameters: {sorted(unknown)}")
+    q.update(overrides)
+    if float(q["be_ratio"]) != 0.0:
+        raise ValueError("best-effort tasks are added on the host (taskgen.table3)")
+    N, S = int(n_tasksets), int(q["eta"][1])
+    spec = gcaps_table3_spec(seed=seed, stream=stream, first_index=first_index, n_cpus=q["n_cpus"],
+                             per_cpu_lo=q["tasks_per_cpu"][0], per_cpu_hi=q["tasks_per_cpu"][1],
+                             gpu_ratio_lo=float(q["gpu_ratio"][0]), gpu_ratio_hi=float(q["gpu_ratio"][1]),
+                             util_lo=float(q["util"][0]), util_hi=float(q["util"][1]), period_lo=q["period"][0],
+                             period_hi=q["period"][1], eta_lo=q["eta"][0], eta_hi=q["eta"][1],
+                             gc_lo=float(q["g_over_c"][0]), gc_hi=float(q["g_over_c"][1]),
+                             gm_lo=float(q["gm_over_g"][0]), gm_hi=float(q["gm_over_g"][1]), theta_us=q["theta_us"],
+                             eps_us=q["eps_us"], slice_us=q["slice_us"])
+    count = torch.empty(N, dtype=torch.int32, device=device)
+    rc = _lib.gcaps_table3_count_device(ctx, ctypes.byref(spec), N, count.data_ptr())
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    gcaps_status(ctx)  # waits for the context's stream
+    groups = {}
+    kinds = {np.uint32: torch.int32, np.int32: torch.int32, np.uint8: torch.uint8}  # uint32 bits in int32 tensors
+    for n in torch.unique(count).tolist():
+        idx = torch.nonzero(count == n).flatten()
+        M = int(idx.numel())
+        idx32 = idx.to(torch.int32).contiguous()
+        shapes = {1: (M,), 2: (M, n), 3: (M, n, S)}
+        batch = {name: torch.empty(shapes[ndim], dtype=kinds[dtype], device=device) for name, dtype, ndim in _FIELDS}
+        b = gcaps_batch(n_tasksets=M, n_tasks=n, max_gseg=S)
+        for name, _, _ in _FIELDS:
+            setattr(b, name, batch[name].data_ptr() if batch[name].numel() else None)
+        torch.cuda.current_stream().synchronize()  # idx32 was made on torch's stream
+        rc = _lib.gcaps_table3_generate_device(ctx, ctypes.byref(spec), idx32.data_ptr(), ctypes.byref(b))
+        if rc != GCAPS_OK:
+            raise GcapsError(rc)
+        gcaps_status(ctx)
+        groups[int(n)] = (idx, batch)
+    return groups
 
 
 def to_host(dbatch):

@@ -25,6 +25,7 @@
 #include "gprio_fast.hip.inc"
 #include "sim.hip.inc"
 #include "taskgen_device.hip.inc"
+#include "taskgen_table3.hip.inc"
 #include "valu_probe.hip.inc"
 
 namespace {
@@ -534,6 +535,31 @@ int for_chunks(gcaps_ctx *ctx, const gcaps_batch *b, F run) {
   }
   if (!isolated) ctx->next_prepared = prepared; /* a recorded call changes nothing for the others */
   return GCAPS_OK;
+}
+
+/* A call of one launch that reports through gcaps_status: a status block of its own, reset first; nothing
+ * prepares the block of the call after it. */
+int begin_single_call(gcaps_ctx *ctx) {
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(ctx->stream, &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    capture = hipStreamCaptureStatusNone;
+  }
+  ctx->capturing = capture != hipStreamCaptureStatusNone;
+  const bool isolated = ctx->capturing || ctx->static_call;
+  if (isolated) {
+    ctx->status_block = 2u;
+  } else {
+    ctx->status_parity ^= 1u;
+    ctx->status_block = ctx->status_parity;
+  }
+  ctx->last_status = status_of(ctx);
+  ctx->next_status = nullptr;
+  ctx->wide_only = true;
+  ctx->last_n_tasksets = 0;
+  const int rc = begin_chunk(ctx, true);
+  if (!isolated) ctx->next_prepared = false;
+  return rc;
 }
 
 int run_device(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
@@ -1128,6 +1154,57 @@ extern "C" int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *sp
   else
     hipLaunchKernelGGL(gen::generate_kernel, grid, block, (size_t)b->n_tasks * 64 * sizeof(u32), ctx->stream, *b, *sp,
                        (u32 *)nullptr, 0u);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+namespace {
+int check_table3(const gcaps_table3_spec *sp) {
+  if (!sp) return GCAPS_EINVAL;
+  if (sp->n_cpus == 0 || sp->n_cpus > 8 || sp->per_cpu_lo == 0 || sp->per_cpu_lo > sp->per_cpu_hi ||
+      (uint64_t)sp->n_cpus * sp->per_cpu_hi > 255 || sp->eta_lo == 0 || sp->eta_lo > sp->eta_hi || sp->eta_hi > 255 ||
+      sp->period_lo == 0 || sp->period_lo > sp->period_hi || !(sp->util_lo > 0.0) || !(sp->util_lo <= sp->util_hi) ||
+      !(sp->gpu_ratio_lo >= 0.0) || !(sp->gpu_ratio_lo <= sp->gpu_ratio_hi) || !(sp->gpu_ratio_hi <= 1.0) ||
+      !(sp->gc_lo >= 0.0) || !(sp->gc_lo <= sp->gc_hi) || !(sp->gm_lo >= 0.0) || !(sp->gm_lo <= sp->gm_hi) ||
+      !(sp->gm_hi <= 1.0) || sp->slice_us == 0)
+    return GCAPS_EINVAL;
+  return GCAPS_OK;
+}
+}  // namespace
+
+extern "C" int gcaps_table3_count_device(gcaps_ctx *ctx, const gcaps_table3_spec *sp, uint32_t n_tasksets,
+                                         uint32_t *d_n_tasks) {
+  if (!ctx || !d_n_tasks || n_tasksets == 0) return GCAPS_EINVAL;
+  int rc = check_table3(sp);
+  if (rc != GCAPS_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  rc = begin_single_call(ctx); /* gcaps_status then reports on this call (nothing to report: it waits) */
+  if (rc != GCAPS_OK) return rc;
+  hipLaunchKernelGGL(gen::table3_count_kernel, dim3((n_tasksets + 63u) / 64u), dim3(64), 0, ctx->stream, *sp, n_tasksets,
+                     d_n_tasks);
+  return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+}
+
+extern "C" int gcaps_table3_generate_device(gcaps_ctx *ctx, const gcaps_table3_spec *sp, const uint32_t *d_index,
+                                            const gcaps_batch *b) {
+  if (!ctx || !b) return GCAPS_EINVAL;
+  int rc = check_table3(sp);
+  if (rc != GCAPS_OK) return rc;
+  if (b->n_tasksets == 0 || b->n_tasks < sp->n_cpus * sp->per_cpu_lo || b->n_tasks > sp->n_cpus * sp->per_cpu_hi ||
+      b->max_gseg < sp->eta_hi || b->max_gseg > 255)
+    return GCAPS_EINVAL;
+  if (!b->theta_us || !b->eps_us || !b->slice_us || !b->cpu_us || !b->period_us || !b->deadline_us || !b->prio ||
+      !b->core || !b->n_gseg || !b->gm_us || !b->ge_us)
+    return GCAPS_EINVAL;
+  const size_t lds = gen::table3_lds_bytes(b->n_tasks);
+  if (lds > 65536) return GCAPS_EINVAL; /* 64 tasks */
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  /* a generator call stands alone: it reports through the status block of a call of its own */
+  rc = begin_single_call(ctx);
+  if (rc != GCAPS_OK) return rc;
+  hipLaunchKernelGGL(gen::table3_generate_kernel, dim3((b->n_tasksets + 63u) / 64u), dim3(64), lds, ctx->stream, *b, *sp,
+                     d_index, status_of(ctx) + fast::ST_FIRST_BAD);
   return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
 }
 

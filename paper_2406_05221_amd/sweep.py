@@ -7,7 +7,9 @@ Columns: the default round-robin TSG scheduling (Sec. 5.2) and GCAPS (Sec. 5.3),
 busy-waiting and self-suspension, and GCAPS with the GPU-segment priority assignment tried for the
 tasksets that fail with equal priorities (Sec. 4.3 / 5.4, the procedure of Sec. 6.1).  Everything
 is computed by the GPU library; this module only draws inputs, groups them by task count (a batch
-of the library has one task count) and averages verdicts.
+of the library has one task count) and averages verdicts.  Without best-effort tasks the inputs are
+generated on the device as well (``--host-inputs`` to draw them on the host and copy them: the same
+tasksets bit for bit), so that no taskset crosses the bus; only the verdicts come back.
 
 Best-effort tasks (``--param be_ratio``, the last experiment of Sec. 6.1) run below every real-time
 task and have no deadline.  Under round-robin TSG scheduling their GPU segments take part in the time
@@ -53,15 +55,44 @@ def verdicts(ctx, groups):
     return out
 
 
-def sweep(ctx, param, values, n_tasksets, seed=0, **fixed):
+def verdicts_device(ctx, groups, total):
+    """The same for groups generated on the device ({n: (index tensor, device batch)} from
+    ``binding.gcaps_table3_device``): device entry points only, the verdicts are copied back."""
+    import torch
+    out = {c: np.zeros(total, np.uint8) for c in COLUMNS}
+    for idx, d in groups.values():
+        N, n = d["cpu_us"].shape
+        rows = idx.cpu().numpy()
+        resp = torch.empty((2, N, n), dtype=torch.int64, device=idx.device)
+        sched = torch.empty((2, N), dtype=torch.uint8, device=idx.device)
+        gprio = torch.empty((N, n), dtype=torch.int32, device=idx.device)
+        found = torch.empty((N,), dtype=torch.uint8, device=idx.device)
+        torch.cuda.synchronize()  # the tensors were made on torch's stream, the library works on the context's
+        for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
+            B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, resp, sched)
+            # separate GPU-segment priorities only where the test with equal priorities failed
+            B.gcaps_gprio_assign_batch_device(ctx, d, wait, sched[0], gprio, resp[0], found)
+            B.gcaps_status(ctx)
+            out[f"gcaps_{name}"][rows] = sched[0].cpu().numpy()
+            out[f"tsg_rr_{name}"][rows] = sched[1].cpu().numpy()
+            out[f"gcaps_{name}+prio"][rows] = found.cpu().numpy()
+    return out
+
+
+def sweep(ctx, param, values, n_tasksets, seed=0, host_inputs=False, **fixed):
     """One row per value of `param` (a key of ``taskgen.TABLE3``; range parameters are set to the
     single value): the share of schedulable tasksets per column.  `fixed`: other Table 3 parameters
-    to hold at values of the caller's choice."""
+    to hold at values of the caller's choice.  The tasksets are generated on the device unless
+    best-effort tasks are asked for or `host_inputs` is set."""
     rows = []
     for k, v in enumerate(values):
         value = (v, v) if isinstance(taskgen.TABLE3[param], tuple) else v
-        groups = taskgen.table3(n_tasksets, seed=seed, stream=300 + k, **{**fixed, param: value})
-        res = verdicts(ctx, groups)
+        params = {**fixed, param: value}
+        if host_inputs or float(params.get("be_ratio", 0.0)) != 0.0:
+            res = verdicts(ctx, taskgen.table3(n_tasksets, seed=seed, stream=300 + k, **params))
+        else:
+            groups = B.gcaps_table3_device(ctx, n_tasksets, seed=seed, stream=300 + k, **params)
+            res = verdicts_device(ctx, groups, n_tasksets)
         rows.append((v, {c: float(res[c].mean()) for c in COLUMNS}))
     return rows
 
@@ -74,6 +105,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--util", type=float, default=None, help="hold the utilisation per CPU at this value")
     ap.add_argument("--eps-us", type=int, default=None, help="hold the runlist-update delay at this value")
+    ap.add_argument("--host-inputs", action="store_true", help="draw the tasksets on the host and copy them")
     args = ap.parse_args()
     cast = int if isinstance(taskgen.TABLE3[args.param], int) or args.param in ("tasks_per_cpu", "period", "eta") \
         else float
@@ -85,7 +117,7 @@ def main():
             fixed["util"] = (args.util, args.util)
         if args.eps_us is not None and args.param != "eps_us":
             fixed["eps_us"] = args.eps_us
-        rows = sweep(ctx, args.param, values, args.tasksets, args.seed, **fixed)
+        rows = sweep(ctx, args.param, values, args.tasksets, args.seed, host_inputs=args.host_inputs, **fixed)
     finally:
         B.gcaps_destroy(ctx)
     print(f"| {args.param} | " + " | ".join(COLUMNS) + " |")

@@ -23,8 +23,9 @@ _lib = None
 
 def build(force=False):
     if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
-        subprocess.run(["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
-                        "-o", _LIB_PATH, _SRC], check=True)
+        # -ffp-contract=off: no fused multiply-add, so that the device generator can match bit for bit
+        subprocess.run(["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-pthread", "-Wall",
+                        "-Wextra", "-o", _LIB_PATH, _SRC], check=True)
     return _LIB_PATH
 
 

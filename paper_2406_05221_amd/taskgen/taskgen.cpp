@@ -9,6 +9,12 @@
  * Every taskset is generated from its own counter-based stream
  * (seed, stream id, taskset index) -> splitmix64, so any taskset can be
  * regenerated alone and the result does not depend on the thread count.
+ *
+ * The library's device generator (csrc/taskgen_device.hip.inc) produces the same batches bit for
+ * bit.  What makes that possible: the random stream is integer arithmetic; every real-valued step
+ * is a fixed sequence of IEEE-754 double additions, multiplications and divisions (correctly
+ * rounded on both machines; no fused multiply-add: this file is built with -ffp-contract=off);
+ * and logarithm and power are the two routines below, not a math library's.
  */
 #include <stdint.h>
 
@@ -41,6 +47,51 @@ struct Rng {
     return lo + (uint32_t)(uniform() * (double)(hi - lo + 1));
   }
 };
+
+/*
+ * log2(x) for a finite x > 0 and 2^x for |x| < 1000, to about 1e-13: enough for drawing periods
+ * and utilisations, and the same bits wherever IEEE double arithmetic is.
+ *   x = m 2^e, m in (sqrt(1/2), sqrt(2)]:  log2 x = e + (2/ln 2) t (1 + t^2/3 + ... + t^14/15), t = (m-1)/(m+1)
+ *   x = i + f, f in [0,1):                 2^x = 2^i (1 + z (1 + z/2 (1 + ... z/14))), z = f ln 2
+ */
+double gen_log2(double x) {
+  uint64_t bits;
+  static_assert(sizeof bits == sizeof x, "IEEE double");
+  __builtin_memcpy(&bits, &x, sizeof bits);
+  int e = (int)((bits >> 52) & 0x7ff) - 1023;
+  bits = (bits & 0x000fffffffffffffull) | 0x3ff0000000000000ull;
+  double m;
+  __builtin_memcpy(&m, &bits, sizeof m);
+  if (m > 1.4142135623730951) {
+    m = m * 0.5;
+    e += 1;
+  }
+  const double t = (m - 1.0) / (m + 1.0), t2 = t * t;
+  double p = 1.0 / 15.0;
+  p = p * t2 + 1.0 / 13.0;
+  p = p * t2 + 1.0 / 11.0;
+  p = p * t2 + 1.0 / 9.0;
+  p = p * t2 + 1.0 / 7.0;
+  p = p * t2 + 1.0 / 5.0;
+  p = p * t2 + 1.0 / 3.0;
+  p = p * t2 + 1.0;
+  return (double)e + 2.8853900817779268 * (t * p);
+}
+
+double gen_exp2(double x) {
+  const double fl = std::floor(x);
+  const double z = (x - fl) * 0.6931471805599453;
+  double p = 1.0;
+  for (int k = 14; k >= 1; --k) p = 1.0 + (z * p) / (double)k;
+  uint64_t bits;
+  __builtin_memcpy(&bits, &p, sizeof bits); /* p in [1, 2]: scaling by 2^i is an add to the exponent */
+  bits += (uint64_t)((int64_t)fl) << 52;
+  __builtin_memcpy(&p, &bits, sizeof p);
+  return p;
+}
+
+/* r^(1/k) for r in [0, 1) */
+double gen_root(double r, uint32_t k) { return r > 0.0 ? gen_exp2(gen_log2(r) / (double)k) : 0.0; }
 
 struct Spec {
   uint64_t seed, stream, first_index;
@@ -75,7 +126,7 @@ void one_taskset(const Spec &sp, const Out &o, uint32_t k) {
   o.eps[k] = ovh;
   o.slice[k] = sp.slice_fixed ? sp.slice_fixed[k] : sp.slice;
 
-  const double ln_lo = std::log((double)sp.t_lo), ln_hi = std::log((double)sp.t_hi);
+  const double l2_lo = gen_log2((double)sp.t_lo), l2_hi = gen_log2((double)sp.t_hi);
   for (uint32_t c = 0; c < sp.n_cores; ++c) {
     double U = sp.util_fixed ? sp.util_fixed[k] : rng.uniform(sp.util_lo, sp.util_hi);
     /* UUniFast: utilisations of the tasks of this core, summing to U */
@@ -84,13 +135,13 @@ void one_taskset(const Spec &sp, const Out &o, uint32_t k) {
       const uint32_t i = c * sp.tasks_per_core + j;
       double u;
       if (j + 1 < sp.tasks_per_core) {
-        double next = sum * std::pow(rng.uniform(), 1.0 / (double)(sp.tasks_per_core - 1 - j));
+        double next = sum * gen_root(rng.uniform(), sp.tasks_per_core - 1 - j);
         u = sum - next;
         sum = next;
       } else {
         u = sum;
       }
-      double t = std::floor(std::exp(rng.uniform(ln_lo, ln_hi)));
+      double t = std::floor(gen_exp2(rng.uniform(l2_lo, l2_hi))); /* log-uniform */
       uint32_t T = (uint32_t)std::min((double)sp.t_hi, std::max((double)sp.t_lo, t));
       uint32_t eta = rng.integer(sp.eta_lo, sp.eta_hi);
       uint32_t W = (uint32_t)std::floor(u * (double)T + 0.5); /* total WCET C + G */
@@ -98,6 +149,7 @@ void one_taskset(const Spec &sp, const Out &o, uint32_t k) {
       double share = sp.share_fixed ? sp.share_fixed[k] : rng.uniform(sp.share_lo, sp.share_hi);
       uint32_t g = (uint32_t)std::floor(share * (double)W + 0.5);
       g = std::min(std::max(g, 2 * eta), W - 1);
+      if (eta == 0) g = 0; /* a CPU-only task keeps its whole demand as CPU time */
       o.cpu[to + i] = W - g;
       o.period[to + i] = T;
       o.deadline[to + i] = T;
@@ -197,7 +249,7 @@ void one_table3(const Table3 &sp, const Out &o, uint32_t *count, uint32_t k) {
     for (uint32_t j = 0; j < m; ++j) {
       double u = sum;
       if (j + 1 < m) {
-        const double next = sum * std::pow(rng.uniform(), 1.0 / (double)(m - 1 - j));
+        const double next = sum * gen_root(rng.uniform(), m - 1 - j);
         u = sum - next;
         sum = next;
       }

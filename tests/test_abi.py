@@ -22,7 +22,7 @@ def binding():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "gcaps_rta.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gcaps_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(gcaps_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_functions_are_exported(binding):

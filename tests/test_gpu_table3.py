@@ -54,10 +54,68 @@ def test_every_analysis_on_table3_tasksets(oracle, gpu):
         assert rescued > 0
 
 
+@pytest.mark.parametrize("overrides", [{}, dict(util=(0.3, 0.35), eps_us=200), dict(n_cpus=2, tasks_per_cpu=(1, 9), eta=(2, 4)),
+                                       dict(n_cpus=8, tasks_per_cpu=(2, 3), gpu_ratio=(0.0, 1.0), period=(5_000, 9_000))])
+def test_table3_tasksets_generated_on_the_device_are_the_hosts(gpu, overrides):
+    """gcaps_table3_count_device / gcaps_table3_generate_device against the host generator: the same grouping by
+    task count and the same batches, every field, bit for bit."""
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    N = 6_000
+    host = taskgen.table3(N, seed=11, stream=301, first_index=77_000, **overrides)
+    dev = B.gcaps_table3_device(ctx, N, seed=11, stream=301, first_index=77_000, **overrides)
+    assert sorted(dev) == sorted(host)
+    for n in host:
+        idx, batch = host[n]
+        d_idx, d_batch = dev[n]
+        assert np.array_equal(d_idx.cpu().numpy(), idx)
+        got = B.to_host(d_batch)
+        for name in batch:
+            assert np.array_equal(got[name], batch[name]), (n, name)
+
+
+def test_table3_generation_rejects_a_wrong_task_count(gpu):
+    import ctypes
+    import torch
+    from paper_2406_05221_amd import taskgen
+    B, ctx, _ = gpu
+    host = taskgen.table3(300, seed=1)
+    by_size = sorted(host, key=lambda m: len(host[m][0]))
+    n, other = by_size[-1], by_size[-2]  # the two most frequent task counts
+    assert len(host[n][0]) >= 20 and len(host[other][0]) >= 5
+    wrong = host[other][0][:5]  # tasksets of another count
+    idx = torch.from_numpy(np.concatenate([host[n][0][:20], wrong]).astype(np.int32)).cuda()
+    assert idx.numel() == 25
+    q = taskgen.TABLE3
+    spec = B.gcaps_table3_spec(seed=1, stream=300, first_index=0, n_cpus=q["n_cpus"], per_cpu_lo=q["tasks_per_cpu"][0],
+                               per_cpu_hi=q["tasks_per_cpu"][1], gpu_ratio_lo=q["gpu_ratio"][0],
+                               gpu_ratio_hi=q["gpu_ratio"][1], util_lo=q["util"][0], util_hi=q["util"][1],
+                               period_lo=q["period"][0], period_hi=q["period"][1], eta_lo=q["eta"][0], eta_hi=q["eta"][1],
+                               gc_lo=q["g_over_c"][0], gc_hi=q["g_over_c"][1], gm_lo=q["gm_over_g"][0],
+                               gm_hi=q["gm_over_g"][1], theta_us=200, eps_us=1000, slice_us=1024)
+    M, S = 25, 3
+    kinds = {np.uint32: torch.int32, np.int32: torch.int32, np.uint8: torch.uint8}
+    shapes = {1: (M,), 2: (M, n), 3: (M, n, S)}
+    batch = {name: torch.zeros(shapes[ndim], dtype=kinds[dtype], device="cuda:0") for name, dtype, ndim in B._FIELDS}
+    b = B.gcaps_batch(n_tasksets=M, n_tasks=n, max_gseg=S)
+    for name, _, _ in B._FIELDS:
+        setattr(b, name, batch[name].data_ptr())
+    torch.cuda.synchronize()
+    assert B._lib.gcaps_table3_generate_device(ctx, ctypes.byref(spec), idx.data_ptr(), ctypes.byref(b)) == B.GCAPS_OK
+    with pytest.raises(B.GcapsError) as e:
+        B.gcaps_status(ctx)
+    assert e.value.code == B.GCAPS_ETASK and e.value.first_bad == 20
+    got = B.to_host(batch)
+    assert (got["period_us"][20:] == 0).all() and (got["period_us"][:20] > 0).all()
+    spec.n_cpus = 9
+    assert B._lib.gcaps_table3_generate_device(ctx, ctypes.byref(spec), idx.data_ptr(), ctypes.byref(b)) == B.GCAPS_EINVAL
+
+
 def test_sweep_matches_the_oracle(oracle, gpu):
     from paper_2406_05221_amd import sweep, taskgen
     B, ctx, _ = gpu
     rows = sweep.sweep(ctx, "util", [0.2, 0.4], 600, seed=5)
+    assert rows == sweep.sweep(ctx, "util", [0.2, 0.4], 600, seed=5, host_inputs=True)
     for k, (value, shares) in enumerate(rows):
         groups = taskgen.table3(600, seed=5, stream=300 + k, util=(value, value))
         want = oracle_verdicts(oracle, groups)

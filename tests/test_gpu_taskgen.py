@@ -1,7 +1,6 @@
-"""Tasksets generated on the device (gcaps_taskgen_device): the recipe and the random streams of the host
-generator.  Integer random draws are identical on both sides; values that pass through log / exp / pow may differ
-by a unit where the two math libraries round differently.  Results of the library on a device-generated batch are
-compared with the oracle on that same batch, copied back."""
+"""Tasksets generated on the device (gcaps_taskgen_device): the host generator's batches, bit for bit (same
+random streams, same sequence of IEEE double operations, the same logarithm and power routines on both
+sides).  Results of the library on a device-generated batch equal the oracle's on the host-generated one."""
 import numpy as np
 import pytest
 
@@ -12,8 +11,9 @@ pytestmark = pytest.mark.gpu
 BOTH, BUSY, SUSPEND = 3, 0, 1
 
 
-@pytest.mark.parametrize("k,N,first", [(1, 1000, 0), (2, 9000, 0), (3, 20_000, 300_000), (4, 1_500, 7), (5, 21_600, 1_000_000)])
-def test_same_recipe_as_the_host_generator(gpu, k, N, first):
+@pytest.mark.parametrize("k,N,first", [(1, 1000, 0), (2, 9000, 0), (3, 200_000, 300_000), (4, 20_000, 7),
+                                       (5, 216_000, 1_000_000)])
+def test_same_batches_as_the_host_generator(gpu, k, N, first):
     import torch
     from paper_2406_05221_amd import taskgen
     B, ctx, stream = gpu
@@ -23,23 +23,8 @@ def test_same_recipe_as_the_host_generator(gpu, k, N, first):
     stream.synchronize()
     dev = B.to_host(d)
     host = taskgen.generate(N, **params)
-    # integer draws and everything derived from them alone
-    for name in ("theta_us", "eps_us", "slice_us", "core", "n_gseg", "deadline_us"):
-        ref = host[name] if name != "deadline_us" else dev["period_us"]
-        assert (dev[name] == ref).all(), name
-    # values that went through the math library: equal almost everywhere, one unit apart at most... in the period;
-    # a period that differs moves W = round(u T) with it
-    same_T = dev["period_us"] == host["period_us"]
-    assert same_T.mean() > 0.999
-    assert (np.abs(dev["period_us"].astype(np.int64) - host["period_us"]) <= 1).all()
-    total_dev = dev["cpu_us"].astype(np.int64) + dev["gm_us"].sum(2) + dev["ge_us"].sum(2)
-    total_host = host["cpu_us"].astype(np.int64) + host["gm_us"].sum(2) + host["ge_us"].sum(2)
-    assert (np.abs(total_dev - total_host)[same_T] <= 1).all()
-    rows = np.ones(N, bool)  # tasksets that are identical in every field
     for name in dev:
-        eq = dev[name] == host[name]
-        rows &= eq.reshape(N, -1).all(axis=1)
-    assert rows.mean() > 0.98, rows.mean()
+        assert np.array_equal(dev[name], host[name]), name
     # the task model holds on the device batch
     eta = dev["n_gseg"]
     assert (dev["cpu_us"] >= 1).all() and (dev["period_us"] >= params["period"][0]).all()
@@ -84,6 +69,29 @@ def test_regenerated_in_pieces_and_analysed_where_it_is(oracle, gpu):
     again = B.gcaps_taskgen_device(ctx, N, out=whole, **params)
     stream.synchronize()
     assert all((B.to_host(again)[k] == host[k]).all() for k in host)
+
+
+def test_relaxed_recipes_and_cpu_only_tasks_match_too(oracle, gpu):
+    """Ranges other than the named workloads', CPU-only tasks (eta = 0: the whole demand stays CPU time) and a
+    shape whose values do not fit LDS (80 tasks: the kernel that stores word by word)."""
+    import torch
+    from paper_2406_05221_amd import taskgen
+    B, ctx, stream = gpu
+    for N, kw in ((30_011, dict(n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.25, 0.85), eta=(0, 3), share=(0.05, 0.5),
+                                period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024, seed=3, stream=1000)),
+                  (2_003, dict(n_cores=8, tasks_per_core=10, max_gseg=5, util=(0.1, 0.6), eta=(0, 5), share=(0.2, 0.7),
+                               period=(500, 2_000_000), overhead=(300, 300), slice_us=2048, seed=4, stream=5)),
+                  (777, dict(n_cores=1, tasks_per_core=9, max_gseg=1, util=(0.5, 0.99), eta=(1, 1), share=(0.1, 0.2),
+                             period=(1_000, 1_001), overhead=(0, 0), slice_us=64, seed=5, stream=6))):
+        with torch.cuda.stream(stream):
+            d = B.gcaps_taskgen_device(ctx, N, first_index=123_456_789, **kw)
+        stream.synchronize()
+        dev, host = B.to_host(d), taskgen.generate(N, first_index=123_456_789, **kw)
+        for name in dev:
+            assert np.array_equal(dev[name], host[name]), (name, kw["n_cores"])
+    # CPU-only tasks keep their whole demand: the utilisation per core is what was asked for
+    cpu_only = host["n_gseg"] == 0
+    assert (host["gm_us"].sum(2)[cpu_only] == 0).all()
 
 
 def test_invalid_arguments(gpu):

@@ -190,3 +190,41 @@ def test_batch_matches_single_calls_and_threads(oracle):
     with pytest.raises(oracle.OracleError) as e:
         oracle.rta_batch(bad, 3, BUSY, threads=3)
     assert e.value.code == oracle.ETASK and e.value.first_bad == 21
+
+
+def test_an_empty_lowest_priority_task_changes_no_bound(oracle):
+    """A task with C = 0 and no GPU segment below every other task (what padding a taskset to a fixed task
+    count would add) leaves every other bound as it was, in all four analyses, and never improves a verdict.
+    Its own bound is the blocking of Lemma 8 plus, under GCAPS with busy-waiting, the GPU work of the tasks
+    above it on other cores (Lemma 11); under round-robin and under self-suspension nothing is charged to a
+    CPU-only task alone on its core, and it always passes."""
+    from paper_2406_05221_amd import taskgen
+    groups = taskgen.table3(1500, seed=2, util=(0.3, 0.3), eps_us=300)
+    for n, (idx, batch) in groups.items():
+        N = len(idx)
+        padded = {}
+        for k, v in batch.items():
+            if v.ndim == 1:
+                padded[k] = v
+            else:
+                pad = np.zeros((N, 1) + v.shape[2:], v.dtype)
+                if k in ("period_us", "deadline_us"):
+                    pad[:] = 500_000
+                if k == "core":
+                    pad[:] = 7  # a core of its own
+                padded[k] = np.concatenate([v, pad], axis=1)  # prio 0: below the real tasks' 1..n
+        for policy in (1, 2):
+            for wait in (0, 1):
+                r0, s0, _ = oracle.rta_batch(batch, policy, wait, threads=8)
+                r1, s1, _ = oracle.rta_batch(padded, policy, wait, threads=8)
+                assert np.array_equal(r1[0][:, :n], r0[0])
+                assert (s1[0] <= s0[0]).all()
+                passed = s0[0] == 1
+                own = r1[0][:, n][passed]
+                if policy == 2:
+                    assert (own == 0).all()  # Lemma 1 with C = G = 0, no same-core task above
+                elif wait == 1:
+                    assert (own == batch["eps_us"][passed]).all()  # Lemma 8 alone
+                else:
+                    assert ((own >= batch["eps_us"][passed]) | (own == -1)).all()
+                    assert (own > batch["eps_us"][passed]).any()  # Lemma 11: GPU work of the other cores

@@ -160,7 +160,7 @@ def test_observed_response_times_stay_below_the_bounds(wait):
     on its core between the end of its GPU work and its closing runlist update keeps the GPU from lower-priority
     segments for that long, which the simulator shows and Lemmas 10 and 13 do not charge
     (test_gcaps_bound_misses_a_delayed_closing_update)."""
-    batch = small_batch(400, seed=11)
+    batch = small_batch(600, seed=11)
     rr = dict(batch, theta_us=np.zeros_like(batch["theta_us"]))
     rng = np.random.default_rng(2)
     checked = 0

@@ -114,3 +114,35 @@ def test_table3_best_effort_tasks():
         last = len(idx) - 1
         assert (rt["cpu_us"][0] == b["cpu_us"][0][~be[0]]).all() and (rt["gm_us"][last] == b["gm_us"][last][~be[last]]).all()
         assert (rt["eps_us"] == b["eps_us"]).all()
+
+
+def test_cpu_only_tasks_keep_their_whole_demand():
+    """eta = 0 is drawn for some tasks: nothing of their demand is set aside for GPU segments that are not there,
+    so the demand per core is the utilisation that was asked for (up to the rounding to whole microseconds)."""
+    from paper_2406_05221_amd import taskgen
+    b = taskgen.generate(4000, n_cores=3, tasks_per_core=4, max_gseg=2, util=(0.6, 0.6), eta=(0, 2), share=(0.5, 0.5),
+                         period=(50_000, 500_000), overhead=(0, 0), slice_us=1024, seed=9, stream=9)
+    demand = b["cpu_us"].astype(np.float64) + b["gm_us"].sum(2) + b["ge_us"].sum(2)
+    per_core = (demand / b["period_us"]).reshape(4000, 3, 4).sum(axis=2)
+    assert np.abs(per_core - 0.6).max() < 1e-3
+    cpu_only = b["n_gseg"] == 0
+    assert cpu_only.mean() > 0.2 and (b["gm_us"].sum(2)[cpu_only] == 0).all() and (b["ge_us"].sum(2)[cpu_only] == 0).all()
+
+
+def test_periods_are_log_uniform_and_splits_sum_to_the_core_utilisation():
+    """The generator's own logarithm and power routines (no math library: the device generator must match bit for
+    bit) are checked through what they produce: log2 of the periods is uniform over the range, and the
+    UUniFast shares of a core have the known mean U / m each."""
+    from paper_2406_05221_amd import taskgen
+    b = taskgen.generate(20_000, n_cores=2, tasks_per_core=5, max_gseg=1, util=(0.5, 0.5), eta=(1, 1), share=(0.1, 0.1),
+                         period=(1_000, 1_000_000), overhead=(0, 0), slice_us=1024, seed=1, stream=2)
+    x = np.log2(b["period_us"].astype(np.float64)).ravel()
+    lo, hi = np.log2(1_000), np.log2(1_000_000)
+    hist, _ = np.histogram(x, bins=20, range=(lo, hi))
+    assert np.abs(hist / x.size - 0.05).max() < 0.004
+    assert b["period_us"].min() >= 1_000 and b["period_us"].max() <= 1_000_000
+    u = (b["cpu_us"].astype(np.float64) + b["gm_us"].sum(2) + b["ge_us"].sum(2)) / b["period_us"]
+    assert np.abs(u.reshape(-1, 2, 5).mean(axis=0) - 0.1).max() < 0.003
+    # the first share of a core is U (1 - r^(1/4)) with r uniform: mean 0.1, second moment 2 U^2 / 30
+    first = u.reshape(-1, 2, 5)[:, :, 0].ravel()
+    assert abs((first ** 2).mean() - 2 * 0.25 / 30) < 6e-4
