@@ -225,8 +225,9 @@ int gcaps_gprio_assign_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, in
  *              it is reported like a task-model violation (GCAPS_ETASK, smallest index)
  *   out_resp   int64 [n_tasksets][n_tasks]: R_i, or GCAPS_RESP_MISS where the bound exceeds D_i
  *   out_sched  uint8 [n_tasksets]: 1 iff no task missed
- * Runs in the general 64-bit kernel (one lane per taskset).  Host / device variants and error
- * reporting as for gcaps_gprio_assign_batch[_device].
+ * Up to 32 tasks per taskset run in a quad-lane 24-bit kernel (tasksets whose numbers leave its range are
+ * handed to the general 64-bit kernel, as gcaps_last_wide_count reports); results are exact on both routes.
+ * Host / device variants and error reporting as for gcaps_gprio_assign_batch[_device].
  */
 int gcaps_gprio_rta_batch(gcaps_ctx *ctx, const gcaps_batch *batch, int wait_mode, const int32_t *gprio,
                           int64_t *out_resp, uint8_t *out_sched, uint32_t *first_bad_taskset);

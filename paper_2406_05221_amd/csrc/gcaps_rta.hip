@@ -23,6 +23,7 @@
 #include "rta_bin.hip.inc"
 #include "gprio_wide.hip.inc"
 #include "gprio_fast.hip.inc"
+#include "gprio_given.hip.inc"
 #include "sim.hip.inc"
 #include "taskgen_device.hip.inc"
 #include "taskgen_table3.hip.inc"
@@ -646,20 +647,61 @@ int run_gprio(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const uint8_t
   });
 }
 
-/* Sec. 5.4 for given GPU priorities: the general kernel over every taskset of the chunk */
+/* Sec. 5.4 for given GPU priorities: the quad-lane kernel over every taskset of the chunk (up to 32 tasks), then
+ * the general kernel over what it listed; other shapes: the general kernel alone */
 int run_gprio_given(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const int32_t *d_gprio, int64_t *d_resp,
                     uint8_t *d_sched) {
   const u64 n = b->n_tasks;
   return for_chunks(ctx, b, [&](const gcaps_batch *sub, u64 c0) {
     if (begin_chunk(ctx, c0 == 0) != GCAPS_OK) return (int)GCAPS_EDEVICE;
-    ctx->wide_only = true;
-    const u32 slots = wide_slots(ctx, sub->n_tasksets);
+    const u32 N = sub->n_tasksets;
+    const int *gp = (const int *)(d_gprio + c0 * n);
+    long long *resp = (long long *)(d_resp + c0 * n);
+    u32 *status = status_of(ctx);
+    const size_t lds = gprio::given_lds_bytes(sub->n_tasks);
+    ctx->wide_only = sub->n_tasks > 32 || lds > (size_t)ctx->lds_limit;
+    const u32 *d_list = nullptr, *d_count = nullptr;
+    u32 items = N;
+    if (!ctx->wide_only) {
+      int rc = ctx->pool.wide_list.reserve((size_t)N * sizeof(u32), !ctx->capturing);
+      if (rc != GCAPS_OK) return rc;
+      const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+      const bool small = sub->n_tasks <= 20;
+      const void *fn = small ? (busy ? (const void *)gprio::gprio_given_fast_kernel<true, 5>
+                                     : (const void *)gprio::gprio_given_fast_kernel<false, 5>)
+                             : (busy ? (const void *)gprio::gprio_given_fast_kernel<true, 8>
+                                     : (const void *)gprio::gprio_given_fast_kernel<false, 8>);
+      int per_cu = 0;
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds) != hipSuccess || per_cu < 1) {
+        (void)hipGetLastError();
+        per_cu = 1;
+      }
+      u32 blocks = (u32)ctx->n_cu * (u32)per_cu;
+      const u32 tiles = (N + 15u) / 16u;
+      if (blocks > tiles) blocks = tiles;
+      const dim3 grid(blocks), block(64);
+      u32 *wl = (u32 *)ctx->pool.wide_list.ptr;
+#define GCAPS_GIVEN_LAUNCH(BUSY, NS)                                                                            \
+  hipLaunchKernelGGL((gprio::gprio_given_fast_kernel<BUSY, NS>), grid, block, lds, ctx->stream, *sub, gp, resp, \
+                     d_sched + c0, status, wl, ctx->ts_offset)
+      if (small) {
+        if (busy) GCAPS_GIVEN_LAUNCH(true, 5); else GCAPS_GIVEN_LAUNCH(false, 5);
+      } else {
+        if (busy) GCAPS_GIVEN_LAUNCH(true, 8); else GCAPS_GIVEN_LAUNCH(false, 8);
+      }
+#undef GCAPS_GIVEN_LAUNCH
+      if (hipGetLastError() != hipSuccess) return (int)GCAPS_EDEVICE;
+      d_list = wl;
+      d_count = status + fast::ST_WIDE_COUNT;
+      items = N < 65536u ? N : 65536u;
+    }
+    const u32 slots = wide_slots(ctx, items);
     wide::Scratch ws;
     int rc = wide_columns(ctx, sub->n_tasks, slots, &ws);
     if (rc != GCAPS_OK) return rc;
-    hipLaunchKernelGGL(gprio::gprio_given_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *sub, wait_mode,
-                       (const int *)(d_gprio + c0 * n), (long long *)(d_resp + c0 * n), d_sched + c0,
-                       status_of(ctx), ws, ctx->ts_offset, ctx->next_status, (u32)fast::kStatusWords);
+    hipLaunchKernelGGL(gprio::gprio_given_kernel, dim3(slots / 256), dim3(256), 0, ctx->stream, *sub, wait_mode, gp, resp,
+                       d_sched + c0, status, ws, d_list, d_count, ctx->ts_offset, ctx->next_status,
+                       (u32)fast::kStatusWords);
     return hipGetLastError() == hipSuccess ? (int)GCAPS_OK : (int)GCAPS_EDEVICE;
   });
 }
