@@ -90,6 +90,11 @@ struct Sim {
   std::deque<int> ring; /* head = TSG on the GPU */
   tick_t slice_used = 0;
   tick_t switch_left = 0;
+  /* Eq. 3 charges a task L + theta per time slice of every *other* TSG (the switch that brings the
+   * slice in, and the slice) and nothing for the switch that brings in its own slice.  For tasks
+   * flagged here that switch takes no time: the schedule Eq. 3 describes from those tasks' side. */
+  std::vector<char> free_switch;
+  tick_t switch_into(int i) const { return !free_switch.empty() && free_switch[i] ? 0 : theta; }
 
   bool overrun = false;
 
@@ -289,13 +294,13 @@ struct Sim {
         if (s.remaining == 0) {
           ring.pop_front();
           slice_used = 0;
-          if (!ring.empty()) switch_left = theta;
+          if (!ring.empty()) switch_left = switch_into(ring.front());
         } else if (slice_used == L) {
           slice_used = 0;
           if (ring.size() > 1) {
             ring.pop_front();
             ring.push_back(i);
-            switch_left = theta;
+            switch_left = switch_into(ring.front());
           }
         }
       }
@@ -318,7 +323,7 @@ struct Sim {
 
 /* Runs one schedule over tasks given in caller order; results come back in caller order. */
 int run_schedule(std::vector<TaskDef> tasks, int policy, int wait, tick_t theta, tick_t eps, tick_t L,
-                 tick_t horizon, tick_t *max_resp, int64_t *jobs_done) {
+                 tick_t horizon, tick_t *max_resp, int64_t *jobs_done, const int *free_switch = nullptr) {
   const int n = (int)tasks.size();
   for (int i = 0; i < n; ++i) tasks[i].caller = i;
   std::stable_sort(tasks.begin(), tasks.end(), [](const TaskDef &a, const TaskDef &b) { return a.prio > b.prio; });
@@ -332,6 +337,10 @@ int run_schedule(std::vector<TaskDef> tasks, int policy, int wait, tick_t theta,
   sim.def = tasks;
   sim.st.resize(n);
   sim.pending.assign(n, 0);
+  if (free_switch) {
+    sim.free_switch.assign(n, 0);
+    for (int i = 0; i < n; ++i) sim.free_switch[i] = free_switch[sim.def[i].caller] != 0;
+  }
   for (int i = 0; i < n; ++i) {
     sim.n_cores = std::max(sim.n_cores, sim.def[i].core + 1);
     sim.build_program(i);
@@ -358,11 +367,13 @@ int run_schedule(std::vector<TaskDef> tasks, int policy, int wait, tick_t theta,
  * still running (the simulation stops there), or -1 on bad arguments.
  * gprio (may be null: same as prio): priorities of the GPU segments, used by the runlist
  * decisions of the GCAPS policy only.
+ * free_switch (may be null: none): round-robin only; the context switch that brings in a time slice of a
+ * task with a non-zero entry takes no time, the accounting of Eq. 3 seen from those tasks.
  */
-extern "C" int des_run_gprio(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
-                             const int *core, const int *prio, const int *gprio, const int *T, const int *D,
-                             const int *offset, const int *eta, const int *c, const int *gm,
-                             const int *ge, int horizon, int *max_resp, int *jobs_done) {
+extern "C" int des_run_free(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
+                            const int *core, const int *prio, const int *gprio, const int *T, const int *D,
+                            const int *offset, const int *eta, const int *c, const int *gm, const int *ge,
+                            const int *free_switch, int horizon, int *max_resp, int *jobs_done) {
   (void)D;
   if (n <= 0 || n > 255 || max_eta < 0 || L <= 0 || (policy != 1 && policy != 2) ||
       (wait_mode != 0 && wait_mode != 1))
@@ -385,12 +396,20 @@ extern "C" int des_run_gprio(int n, int max_eta, int policy, int wait_mode, int 
   }
   std::vector<tick_t> mr(n);
   std::vector<int64_t> jd(n);
-  const int rc = run_schedule(tasks, policy, wait_mode, theta, eps, L, horizon, mr.data(), jd.data());
+  const int rc = run_schedule(tasks, policy, wait_mode, theta, eps, L, horizon, mr.data(), jd.data(), free_switch);
   for (int i = 0; i < n; ++i) {
     max_resp[i] = (int)mr[i];
     jobs_done[i] = (int)jd[i];
   }
   return rc;
+}
+
+extern "C" int des_run_gprio(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,
+                             const int *core, const int *prio, const int *gprio, const int *T, const int *D,
+                             const int *offset, const int *eta, const int *c, const int *gm,
+                             const int *ge, int horizon, int *max_resp, int *jobs_done) {
+  return des_run_free(n, max_eta, policy, wait_mode, theta, eps, L, core, prio, gprio, T, D, offset, eta, c, gm, ge,
+                      nullptr, horizon, max_resp, jobs_done);
 }
 
 extern "C" int des_run(int n, int max_eta, int policy, int wait_mode, int theta, int eps, int L,

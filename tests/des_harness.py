@@ -14,9 +14,11 @@ def _load():
     return oracle.sim_library()
 
 
-def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon, gprio=None):
+def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon, gprio=None, free_switch=None):
     """tasks: list of dicts with core, prio, T, D, c (eta+1 ints), gm, ge (eta ints each).
     gprio: priorities of the GPU segments (GCAPS runlist decisions), default = prio.
+    free_switch: round-robin only, flags of the tasks whose own time slices are brought in by a switch
+    that takes no time (the accounting of Eq. 3 from those tasks' side), default: none.
     Returns (rc, max_resp[n], jobs_done[n])."""
     n = len(tasks)
     max_eta = max(len(t["ge"]) for t in tasks)
@@ -44,6 +46,10 @@ def run(tasks, *, policy, wait_mode, theta, eps, L, offsets, horizon, gprio=None
     p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
     gp = prio if gprio is None else np.ascontiguousarray(gprio, dtype=np.int32)
     assert gp.size == n
-    rc = _load().des_run_gprio(n, max_eta, policy, wait_mode, theta, eps, L, p(core), p(prio), p(gp), p(T),
-                               p(D), p(off), p(eta), p(c), p(gm), p(ge), horizon, p(mr), p(jd))
+    fs = None if free_switch is None else np.ascontiguousarray(free_switch, dtype=np.int32)
+    assert fs is None or fs.size == n
+    lib = _load()
+    lib.des_run_free.restype = ctypes.c_int
+    rc = lib.des_run_free(n, max_eta, policy, wait_mode, theta, eps, L, p(core), p(prio), p(gp), p(T), p(D), p(off),
+                          p(eta), p(c), p(gm), p(ge), None if fs is None else p(fs), horizon, p(mr), p(jd))
     return rc, mr, jd
