@@ -25,7 +25,9 @@
  *    completes.  An update that leaves the running set unchanged (a lower-priority
  *    task joining the pending list) costs nothing.  The lock is handed to the
  *    highest-priority requester that is able to run on its core.  A task waiting for
- *    the lock behaves like a task waiting for the GPU (spins or sleeps).
+ *    the lock sleeps in either waiting mode (Sec. 5.3 names the lock an rt-mutex;
+ *    busy-waiting is how a task waits for its GPU work): the lower-priority tasks of
+ *    its core run meanwhile.
  *  - Only the task at the head of the running set makes GPU progress.
  *  - Whatever happens at the same instant happens in decreasing CPU priority (equal priorities:
  *    lower caller index first), so a result does not depend on the order the caller lists the tasks in.
@@ -253,8 +255,8 @@ struct Sim {
         st[g].remaining = eps;
       }
     }
-    /* requesters that did not get the lock: spin (busy) or step aside (suspend) */
-    if (policy == 1 && wait == 1) {
+    /* requesters that did not get the lock sleep on it: the core goes to the next task */
+    if (policy == 1) {
       for (int c = 0; c < n_cores; ++c) {
         while (on_core[c] >= 0 && is_update_waiter(on_core[c])) {
           blocked[on_core[c]] = 1;

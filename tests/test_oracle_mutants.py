@@ -165,9 +165,13 @@ def test_unmutated_oracle_passes_the_same_pins(oracle):
 SIM_SRC = os.path.join(ROOT, "oracle", "sim_oracle.cpp")
 
 SIM_MUTANTS = {
-    "no_switch_after_a_completed_segment": ("          if (!ring.empty()) switch_left = theta;\n", "\n"),
-    "rotation_without_switch": ("            ring.push_back(i);\n            switch_left = theta;",
+    "no_switch_after_a_completed_segment": ("          if (!ring.empty()) switch_left = switch_into(ring.front());\n", "\n"),
+    "rotation_without_switch": ("            ring.push_back(i);\n            switch_left = switch_into(ring.front());",
                                 "            ring.push_back(i);\n            switch_left = 0;"),
+    "free_switch_follows_the_own_slice": ("            ring.push_back(i);\n            switch_left = switch_into(ring.front());",
+                                          "            ring.push_back(i);\n            switch_left = switch_into(i);"),
+    "lock_waiter_spins_when_busy_waiting": ("sleep on it: the core goes to the next task */\n    if (policy == 1) {",
+                                            "sleep on it: the core goes to the next task */\n    if (policy == 1 && wait == 1) {"),
     "slice_never_expires": ("        } else if (slice_used == L) {", "        } else if (false) {"),
     "remove_does_not_hand_over": ("      running = k;\n      if (k >= 0) pending[k] = 0;", "      running = -1;"),
     "add_does_not_preempt": ("    } else if (higher_g(i, running)) {\n      pending[running] = 1;",
@@ -198,6 +202,8 @@ SIM_PINS = [
     sim_tests.test_overrun_stops_the_taskset_and_is_flagged,
     sim_tests.test_simultaneous_arrivals_take_the_gpu_in_priority_order,
     sim_tests.test_gcaps_bound_misses_a_delayed_closing_update,
+    sim_tests.test_a_task_waiting_for_the_driver_lock_sleeps_in_either_mode,
+    lambda: des_tests.test_own_slice_switch_outside_eq3(des_tests.des.oracle),
 ]
 
 

@@ -59,6 +59,24 @@ def test_gcaps_with_reversed_gpu_priorities_by_hand():
         assert mort[:, 0].tolist() == [[14, 14], [10, 16]] and (jobs == 1).all() and (flag == 0).all()
 
 
+def test_a_task_waiting_for_the_driver_lock_sleeps_in_either_mode():
+    """Worked by hand, eps = 2.  Core 1: tau_l (lowest, C = 0, one GPU segment of 5) takes the lock for its opening
+    update [0,2).  Core 0: tau_m (C = 3, CPU-only) runs from 0; tau_h (highest, C = 0, one GPU segment of 3) is
+    released at 1 and asks for its opening update while the lock is taken: it sleeps on the lock (an rt-mutex,
+    Sec. 5.3) and tau_m runs on, [1,2).  At 2 tau_h gets the lock: update [2,4) (tau_l's segment runs [2,4) until the
+    update takes effect), GPU [4,7), closing update [7,9): response 8.  Busy-waiting: tau_h keeps core 0 during
+    [4,7), tau_m's last tick is [9,10): response 10 (11 if tau_h had spun on the lock during [1,2)).
+    Self-suspension: tau_m's last tick is [4,5): response 5.  tau_l: GPU [9,12), closing update [12,14): 14."""
+    tasks = [dict(C=0, T=100, prio=3, core=0, gm=[0], ge=[3], off=1),
+             dict(C=3, T=100, prio=2, core=0, gm=[], ge=[], off=0),
+             dict(C=0, T=100, prio=1, core=1, gm=[0], ge=[5], off=0)]
+    b, off = one_taskset(tasks, theta=0, eps=2, L=4)
+    mort, _, flag = oracle.simulate_batch(b, GCAPS, BUSY, 60, offset=off)
+    assert mort[0, 0].tolist() == [8, 10, 14] and flag[0, 0] == 0
+    mort, _, flag = oracle.simulate_batch(b, GCAPS, SUSPEND, 60, offset=off)
+    assert mort[0, 0].tolist() == [8, 5, 14] and flag[0, 0] == 0
+
+
 def test_round_robin_slices_by_hand():
     """The same two tasks under time-sliced round-robin, L = 4, theta = 1.  Low task on the GPU from 1; the
     high task joins the ring at 5.  The low task's slice that began at 5 ends at 9 (it has had 8 ticks), switch
