@@ -24,6 +24,34 @@
  * All times are unsigned integer microseconds.  All arithmetic is exact
  * integer arithmetic; results do not depend on launch shape or batch order.
  *
+ * Where the lemmas as printed leave a choice, the library computes one reading
+ * only (there is no switch for another one):
+ *   - G_i := sum_j (G^m_{i,j} + G^e_{i,j}) (Sec. 3 bounds G_i from above only); under
+ *     GCAPS the task's own 2 * epsilon * eta^g_i (Sec. 5.3) is added to Eq. 1;
+ *   - Lemma 10: the sum over the GPU-using higher-priority tasks of tau_i's core is
+ *     applied to every tau_i; the printed guard eta^g_i > 0 would let a CPU-only task
+ *     ignore the busy-waiting of a task above it on its core;
+ *   - Lemma 7: the jitter J^c_h is applied to self-suspending (GPU-using) tau_h only,
+ *     as Lemma 15 does; CPU-only tasksets then reduce to the classic analysis;
+ *   - Lemma 8: B^C_i = (eta^g_i + 1) * epsilon for every task, GPU-using or not;
+ *   - Lemma 4: the set is the GPU-using tasks outside hpp(tau_i) plus tau_h itself;
+ *   - Lemma 11 is applied as printed, with no condition on tau_i's core.
+ *
+ * What a verdict of 1 means: every bound R_i of the lemmas, under these readings, is
+ * at most D_i.  Two effects that a concrete schedule (gcaps_simulate_batch) shows are
+ * charged by no lemma, so a simulated job can respond later than R_i:
+ *   - round-robin, theta > 0: Eq. 3 counts theta + L per time slice of every other
+ *     TSG and nothing for the switch that brings in the task's own slice; a segment
+ *     of k slices can see up to k more theta than Eq. 3 holds.  With theta = 0, or
+ *     in a schedule that leaves those switches out, no simulated job was seen above
+ *     its bound;
+ *   - GCAPS, epsilon > 0: gcapsGpuSegEnd() is a system call of the task's own thread
+ *     (Sec. 4.2), so a task that is preempted on its core after its GPU work keeps its
+ *     TSGs on the runlist until it runs again, and lower-priority GPU segments wait
+ *     for that long; Lemmas 10 and 13 charge tau_h's GPU segment and its updates, not
+ *     this wait.  Tasks for which every GPU-using task of higher priority is the
+ *     highest-priority task of its core cannot be reached by it.
+ *
  * Plain C, no exceptions, no callbacks.  Every function returns GCAPS_OK (0) or
  * a negative error code and never aborts.  A context is not thread-safe: use
  * one context per host thread.
@@ -117,7 +145,8 @@ void gcaps_destroy(gcaps_ctx *ctx);
  *   out_resp   host int64 [npol][n_tasksets][n_tasks], tasks in caller order: R_i in
  *              microseconds, or a sentinel.  Policies are stored in increasing
  *              selector value (GCAPS before round-robin).
- *   out_sched  host uint8 [npol][n_tasksets]: 1 iff every task met R_i <= D_i
+ *   out_sched  host uint8 [npol][n_tasksets]: 1 iff every task met R_i <= D_i (what the bounds
+ *              cover and what they leave out: head of this file)
  *   first_bad_taskset  may be NULL; on GCAPS_ETASK receives the smallest index of
  *              an invalid taskset
  * On any error no output element is defined.
@@ -251,8 +280,8 @@ int gcaps_gprio_rta_batch_device(gcaps_ctx *ctx, const gcaps_batch *batch, int w
  *   - GCAPS_POLICY_GCAPS: the GPU work of a segment lies between two runlist updates decided as in Alg. 1; an
  *     update that changes the running TSGs takes eps on the caller's core under the driver lock (not
  *     preemptible; the lock goes to the highest-priority requester that holds its core; a requester without
- *     the lock spins or, under self-suspension, steps aside), one that only joins or leaves the pending list
- *     takes no time; only the task whose TSGs are running makes GPU progress;
+ *     the lock sleeps on it in either waiting mode, Sec. 5.3 naming it an rt-mutex, and the lower-priority
+ *     tasks of its core run meanwhile), one that only joins or leaves the pending list takes no time; only the task whose TSGs are running makes GPU progress;
  *   - releases are strictly periodic: tau_i at offset_i, offset_i + T_i, ...; deadline_us is not used and
  *     may be NULL;
  *   - events of one instant take effect in decreasing priority, so results do not depend on caller order.

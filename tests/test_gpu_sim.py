@@ -301,13 +301,16 @@ def test_bench_size_on_sampled_tasksets(oracle, gpu):
     batch = taskgen.generate(N, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.2, 0.4), eta=(1, 3),
                              share=(0.10, 0.60), period=(10_000, 100_000), overhead=(50, 500), slice_us=1024,
                              seed=0, stream=79)
-    sample = np.sort(np.concatenate([np.random.default_rng(3).choice(N, 44, replace=False), [0, 131_071, 131_072, N - 1]]))
+    sample = np.unique(np.concatenate([np.random.default_rng(3).choice(N, 636, replace=False), [0, 131_071, 131_072, N - 1]]))
+    assert sample.size >= 600
     sub = {k: np.ascontiguousarray(v[sample]) for k, v in batch.items()}
-    got = B.gcaps_simulate_batch(ctx, batch, BOTH, SUSPEND, horizon)
-    want = oracle.simulate_batch(sub, BOTH, SUSPEND, horizon, threads=16)
-    assert (got[0][:, sample] == want[0]).all() and (got[1][:, sample] == want[1]).all()
-    assert (got[2][:, sample] == want[2]).all()
-    assert B.gcaps_last_sim_steps(ctx) > N
+    for wait in (BUSY, SUSPEND):
+        print(f"wait {wait}", flush=True)
+        got = B.gcaps_simulate_batch(ctx, batch, BOTH, wait, horizon)
+        want = oracle.simulate_batch(sub, BOTH, wait, horizon, threads=16)
+        assert (got[0][:, sample] == want[0]).all() and (got[1][:, sample] == want[1]).all()
+        assert (got[2][:, sample] == want[2]).all()
+        assert B.gcaps_last_sim_steps(ctx) > N
 
 
 def test_full_size_values_on_sampled_tasksets(oracle, gpu):
@@ -320,7 +323,7 @@ def test_full_size_values_on_sampled_tasksets(oracle, gpu):
     batch = taskgen.generate(N, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.2, 0.4), eta=(1, 3),
                              share=(0.10, 0.60), period=(10_000, 100_000), overhead=(50, 500), slice_us=1024,
                              seed=0, stream=79)
-    sample = np.random.default_rng(8).choice(N, 12, replace=False)
+    sample = np.random.default_rng(8).choice(N, 96, replace=False)
     sub = {k: np.ascontiguousarray(v[sample]) for k, v in batch.items()}
     for wait in (BUSY, SUSPEND):
         print(f"wait {wait}", flush=True)
@@ -338,7 +341,9 @@ def test_full_size_values_on_sampled_tasksets(oracle, gpu):
 
 def test_observed_against_bounds_study(gpu):
     """The study module (observed / bound per analysis on the paper's generation recipe) runs on the library
-    alone; schedulable tasksets exist, observed response times are positive and mostly below their bounds."""
+    alone; schedulable tasksets exist and observed response times are positive.  Tasks seen above their bound are
+    counted and printed, not capped: the simulated system charges two things the lemmas do not (module docstring).
+    Under GCAPS with equal priorities none of them may be a task that a delayed closing update cannot reach."""
     from paper_2406_05221_amd import pessimism, taskgen
     B, ctx, _ = gpu
     groups = taskgen.table3(300, seed=5, util=(0.25, 0.25))
@@ -351,16 +356,16 @@ def test_observed_against_bounds_study(gpu):
             continue  # no taskset of this draw needed separate priorities and got them
         assert r["schedulable"] > 0 and r["tasks"] > 0
         assert 0.0 < r["mean_ratio"] < 1.0
-        assert r["above_bound"] <= r["tasks"] // 20
+        if name in ("gcaps_busy", "gcaps_suspend"):
+            assert r["tasks_clear"] > 100 and r["above_clear"] == 0
 
 
 def test_bounds_hold_at_scale(gpu):
     """The domination pin of the analysis (no job of a schedulable taskset responds later than its bound) on 60,000
     tasksets with microsecond-scale values instead of a few hundred tiny ones: bounds and schedules both from the
-    library.  GCAPS on tasksets whose GPU-using tasks lead their cores, round-robin at theta = 0 (the two things
-    the lemmas do not charge are excluded, as in test_oracle_sim.py)."""
-    from paper_2406_05221_amd import taskgen
-    from test_oracle_sim import gpu_tasks_lead_their_cores
+    library.  GCAPS on the tasks that no delayed closing update can reach, round-robin at theta = 0 (the two
+    things the lemmas do not charge are excluded, as in test_oracle_sim.py)."""
+    from paper_2406_05221_amd import pessimism, taskgen
     B, ctx, _ = gpu
     N = 60_000
     batch = taskgen.generate(N, n_cores=3, tasks_per_core=3, max_gseg=2, util=(0.15, 0.5), eta=(0, 2),
@@ -373,14 +378,16 @@ def test_bounds_hold_at_scale(gpu):
         for wait in (BUSY, SUSPEND):
             resp, sched = B.gcaps_rta_batch(ctx, b, policy, wait)
             ok = sched[0].astype(bool)
+            domain = np.broadcast_to(ok[:, None], resp[0].shape).copy()
             if policy == GCAPS:
-                ok &= gpu_tasks_lead_their_cores(b)
+                domain &= pessimism.clear_of_delayed_updates(b)
             for trial in range(2):
                 off = None if trial == 0 else (rng.random(b["cpu_us"].shape) * b["period_us"]).astype(np.uint32)
                 mort, jobs, flag = B.gcaps_simulate_batch(ctx, b, policy, wait, 400_000, offset=off)
                 assert not flag[0][ok].any()
-                worse = mort[0][ok] > resp[0][ok]
+                worse = mort[0][domain] > resp[0][domain]
                 assert not worse.any(), (policy, wait, trial, int(worse.sum()))
                 assert (jobs[0][ok] >= 1).all()
-            checked += int(ok.sum())
-    assert checked > 15_000
+            checked += int(domain.sum())
+            print(policy, wait, "tasksets", int(ok.sum()), "tasks compared", int(domain.sum()), flush=True)
+    assert checked > 300_000

@@ -146,3 +146,27 @@ def test_periods_are_log_uniform_and_splits_sum_to_the_core_utilisation():
     # the first share of a core is U (1 - r^(1/4)) with r uniform: mean 0.1, second moment 2 U^2 / 30
     first = u.reshape(-1, 2, 5)[:, :, 0].ravel()
     assert abs((first ** 2).mean() - 2 * 0.25 / 30) < 6e-4
+
+
+def test_tasks_clear_of_delayed_updates_by_hand():
+    """The study module's mask of tasks that no delayed closing update can reach: task k is clear when every
+    GPU-using task of higher priority is the highest-priority task of its core."""
+    from paper_2406_05221_amd import pessimism
+    # priorities 6..1; cores 0,1,0,1,0,1; GPU segments: tasks 0 (leads core 0), 2 (second on core 0), 5 (last on core 1)
+    fields = dict(prio=np.array([[6, 5, 4, 3, 2, 1]], np.int32), core=np.array([[0, 1, 0, 1, 0, 1]], np.uint8),
+                  n_gseg=np.array([[1, 0, 2, 0, 0, 1]], np.uint8))
+    # tasks 0..2 have only task 0 as a GPU-using task above them; below task 2 its update can wait for task 0's CPU work
+    assert pessimism.clear_of_delayed_updates(fields).tolist() == [[True, True, True, False, False, False]]
+    # the order of the columns does not matter, only the priorities
+    perm = [3, 5, 0, 2, 4, 1]
+    shuffled = {k: v[:, perm] for k, v in fields.items()}
+    assert pessimism.clear_of_delayed_updates(shuffled).tolist() == [[False, False, True, True, False, True]]
+
+
+def test_tasks_clear_of_delayed_updates_against_the_loop_form():
+    from paper_2406_05221_amd import pessimism
+    from test_oracle_sim import tasks_no_delayed_update_reaches
+    b = taskgen.generate(200, n_cores=3, tasks_per_core=3, max_gseg=2, util=(0.2, 0.5), eta=(0, 2), share=(0.1, 0.5),
+                         period=(40, 400), overhead=(1, 3), slice_us=8, seed=4, stream=5)
+    mask = pessimism.clear_of_delayed_updates(b)
+    assert (mask == tasks_no_delayed_update_reaches(b)).all() and 0.2 < mask.mean() < 0.9
