@@ -20,8 +20,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
-VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # CUs x SIMDs x lanes x clock: 32-bit integer lane-ops/s
+# 32-bit integer lane-operations/s by the unit counts: CUs x SIMDs x lanes x clock = 39.3e12.  What the
+# device sustains per instruction kind is measured by `--row peak` (profiles/int32_peak.md: add 1.36 x this
+# figure, shifts 1.71 x, the 24-bit multiply-add 0.89 x, the 24-bit multiply-high 0.97 x, 32-bit multiplies
+# 0.91-0.96 x: 24-bit and 32-bit multiplies run at the same rate; the four instructions of one interference
+# term 1.13 x).  The rta rows run the probe themselves and report fractions against both.
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3), multiply-add, compare
+
+# VALU work of one step as the hardware counted it (SQ_INSTS_VALU summed over the launches of a step, and the
+# active-lane share SQ_THREAD_CYCLES_VALU / (64 x SQ_ACTIVE_INST_VALU... see the profile files), per workload,
+# 1,000,000 tasksets, mean of the two waiting modes; valid for the kernel sources they were taken with
+# (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
+MEASURED_VALU = dict(csrc_sha256="", per_workload={})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
@@ -59,6 +70,72 @@ def copy_calibration():
     del src, dst
 
 
+def host_threads():
+    """Host threads for the oracle leg: every core this process may run on, or the CPU share that the
+    environment states for the job when that is smaller."""
+    allowed = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    share = os.environ.get("OMP_NUM_THREADS", "")
+    return max(1, min(allowed, int(share)) if share.isdigit() and int(share) > 0 else allowed)
+
+
+WORKLOAD0 = dict(n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.25, 0.85), eta=(0, 3), share=(0.05, 0.5),
+                 period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024, seed=0, stream=1000)
+
+
+def timed_steps(B, ctx, stream, step, steps, warmup):
+    """`warmup` untimed and `steps` timed calls of step() on the context's stream: (seconds of wall time over
+    the timed calls, device milliseconds of each from events on that stream)."""
+    import torch
+    for _ in range(warmup):
+        step()
+    B.gcaps_status(ctx)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        starts[k].record(stream)
+        step()
+        stops[k].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.gcaps_status(ctx)
+    return t1 - t0, [a.elapsed_time(b) for a, b in zip(starts, stops)]
+
+
+def other_workloads(B, taskgen, ctx, stream, steps, warmup, skip):
+    """Device milliseconds per step (both analyses) for the workloads the headline is not quoted on, each
+    generated on the device by the host generator's recipe (the same tasksets bit for bit) at its own shape and
+    at most 1,000,000 tasksets per batch."""
+    import numpy as np
+    import torch
+    res = {}
+    for k in (0, 1, 2, 3, 4, 5):
+        if k == skip:
+            continue
+        if k == 0:
+            N, params = 1_000_000, WORKLOAD0
+        else:
+            N, params = taskgen.config_params(k, min(taskgen.CONFIG_SIZES[k], 1_000_000))
+        d = B.gcaps_taskgen_device(ctx, N, **params)
+        n = params["n_cores"] * params["tasks_per_core"]
+        resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+        sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        row = dict(tasksets=N, n_tasks=n, max_gseg=params["max_gseg"])
+        for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
+            _, dev = timed_steps(B, ctx, stream, lambda: B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait,
+                                                                                 resp, sched), steps, warmup)
+            row[f"device_ms_{name}"] = float(np.mean(dev))
+            row[f"sched_ratio_gcaps_{name}"] = float(sched[0].float().mean().item())
+            row[f"tasksets_via_64bit_kernel_{name}"] = B.gcaps_last_wide_count(ctx)
+        slow = max(row["device_ms_busy"], row["device_ms_suspend"])
+        row["hbm_frac"] = algorithmic_bytes_per_taskset(n, params["max_gseg"], 2) * N / (slow * 1e-3) / 1e9 / HBM_PEAK_GBS
+        res[str(k)] = row
+        del d, resp, sched
+    return res
+
+
 def algorithmic_bytes_per_taskset(n, S, npol):
     """Bytes the path must move per taskset: every input once, every output once."""
     inputs = 3 * 4 + n * (4 * 4 + 2 * 1) + n * S * 2 * 4   # theta, eps, L; C, T, D, prio, core, eta; Gm, Ge
@@ -77,6 +154,8 @@ def main():
                          "schedulable under GCAPS), not a headline")
     ap.add_argument("--tasksets", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-end-to-end", action="store_true", help="skip the timing of the host entry point")
+    ap.add_argument("--no-per-workload", action="store_true", help="skip the device timings of the other workloads")
     ap.add_argument("--binning", type=int, default=0, choices=[0, 1])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run device-to-device copies of 1 GiB (a kernel of known traffic, for scaling "
@@ -127,9 +206,7 @@ def main():
     if args.workload == 0:
         N = args.tasksets or 1_000_000
         cores, per_core, S = 4, 5, 3
-        batch = taskgen.generate(N, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.25, 0.85), eta=(0, 3),
-                                 share=(0.05, 0.5), period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024,
-                                 seed=0, stream=1000)
+        batch = taskgen.generate(N, **WORKLOAD0)
     else:
         N = args.tasksets or min(taskgen.CONFIG_SIZES[args.workload], 1_000_000)
         cores, per_core, S = taskgen.CONFIG_SHAPES[args.workload]
@@ -151,25 +228,13 @@ def main():
 
     modes = {}
     for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
-        for _ in range(args.warmup):
-            B.gcaps_rta_batch_device(ctx, d, policy, wait, d_resp, d_sched)
-        B.gcaps_status(ctx)
-        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            starts[k].record(stream)
-            B.gcaps_rta_batch_device(ctx, d, policy, wait, d_resp, d_sched)
-            stops[k].record(stream)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        B.gcaps_status(ctx)
-        dev_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
-        modes[name] = dict(wall_ms_per_step=(t1 - t0) * 1e3 / args.steps,
+        wall, dev_ms = timed_steps(B, ctx, stream,
+                                   lambda: B.gcaps_rta_batch_device(ctx, d, policy, wait, d_resp, d_sched),
+                                   args.steps, args.warmup)
+        modes[name] = dict(wall_ms_per_step=wall * 1e3 / args.steps,
                            device_ms_per_step=float(np.mean(dev_ms)),
                            device_ms_median=float(np.median(dev_ms)),
-                           tasksets_per_s=N * args.steps / (t1 - t0),
+                           tasksets_per_s=N * args.steps / wall,
                            sched_ratio_gcaps=float(d_sched[0].float().mean().item()),
                            sched_ratio_rr=float(d_sched[1].float().mean().item()),
                            tasksets_via_64bit_kernel=B.gcaps_last_wide_count(ctx))
@@ -183,7 +248,7 @@ def main():
     terms_per_taskset = None
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(16, os.cpu_count() or 1)
+        threads = host_threads()
         sample = min(N, 1_000_000)
         sub = {k: v[:sample] for k, v in batch.items()}
         t0 = time.perf_counter()
@@ -202,8 +267,9 @@ def main():
         same = bool((d_resp[:, :sample].cpu().numpy() == want_r).all() and
                     (d_sched[:, :sample].cpu().numpy() == want_s).all())
         cpu = dict(value=sample / t_all, unit="tasksets/s", cores=threads, kind="oracle",
+                   host_cores_visible=os.cpu_count(),
                    sample=f"first {sample} tasksets of the workload, both analyses, {head} mode, "
-                          f"{threads} std::thread workers over tasksets",
+                          f"{threads} std::thread workers over tasksets (every core the job may use)",
                    one_core_value=one / t_one, one_core_sample=f"first {one} tasksets, 1 thread",
                    gpu_matches_oracle_on_sample=same)
 
@@ -219,12 +285,43 @@ def main():
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
                     traffic=traffic, kernel="gcaps_rta_batch_device (all launches of one step)",
                     algorithmic_bytes_per_taskset=algorithmic_bytes_per_taskset(n, S, P))
-    alu = None
+    # the arithmetic side: the probe's rates are measured now, on this device
+    rates = B.gcaps_valu_probe(ctx)
+    term_mix = rates["lane_ops_per_s"]["term"]
+    alu = dict(peak=VALU_PEAK_LANE_OPS, peak_by="256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz",
+               probe_lane_ops_per_s=rates["lane_ops_per_s"], probe_clock_khz=rates["clock_khz"],
+               probe_cu_count=rates["cu_count"],
+               peak_measured_term_mix=term_mix,
+               note="6 integer ops per interference term evaluated by plain iteration (oracle count); "
+                    "peak_measured_term_mix = the add, 24-bit multiply-high, shift, 24-bit multiply-add of one term "
+                    "in independent chains, measured in this run")
     if terms_per_taskset is not None:
         ops = OPS_PER_TERM * terms_per_taskset * N / (m["device_ms_per_step"] * 1e-3)
-        alu = dict(terms_per_taskset=terms_per_taskset, terms_per_s=ops / OPS_PER_TERM,
-                   int32_lane_ops_per_s=ops, peak=VALU_PEAK_LANE_OPS, frac=ops / VALU_PEAK_LANE_OPS,
-                   note="6 integer ops per interference term evaluated by plain iteration (oracle count)")
+        alu.update(terms_per_taskset=terms_per_taskset, terms_per_s=ops / OPS_PER_TERM, int32_lane_ops_per_s=ops,
+                   frac=ops / VALU_PEAK_LANE_OPS, frac_of_measured_term_mix=ops / term_mix)
+    mv = MEASURED_VALU
+    counted = mv["per_workload"].get(str(args.workload))
+    alu["measured_valu_lane_ops_per_s"] = None
+    if (counted and N == counted["tasksets"] and not args.binning and not args.continue_after_miss
+            and mv["csrc_sha256"] == csrc_sha256()):
+        lane_ops = counted["valu_wave_insts"] * counted["active_lanes"]
+        alu.update(measured_valu_lane_ops_per_s=lane_ops / (m["device_ms_per_step"] * 1e-3),
+                   measured_valu_wave_insts_per_step=counted["valu_wave_insts"],
+                   measured_active_lanes_per_valu_inst=counted["active_lanes"],
+                   measured_frac=lane_ops / (m["device_ms_per_step"] * 1e-3) / VALU_PEAK_LANE_OPS)
+
+    # the host entry point: pack, copy in, analyse, copy out (the PCIe-inclusive rate; never `value`)
+    end_to_end = None
+    if not args.no_end_to_end:
+        B.gcaps_rta_batch(ctx, batch, policy, head_wait)
+        reps = 2
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            B.gcaps_rta_batch(ctx, batch, policy, head_wait)
+        end_to_end = (time.perf_counter() - t0) * 1e3 / reps
+    per_workload = None
+    if not args.no_per_workload:
+        per_workload = other_workloads(B, taskgen, ctx, stream, max(3, args.steps // 2), 2, args.workload)
 
     out = dict(metric="tasksets analysed/sec (both RTAs), 1 MI355X", value=m["tasksets_per_s"], unit="tasksets/s",
                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=m["wall_ms_per_step"],
@@ -234,7 +331,10 @@ def main():
                                     f"waiting mode ({head})",
                            tasksets=N, n_tasks=n, max_gseg=S, policy="gcaps+rr", wait_mode=head,
                            binning=args.binning, continue_after_miss=bool(args.continue_after_miss)),
-               modes=modes, roofline=roofline, int32_valu=alu, cpu_baseline=cpu)
+               modes=modes, roofline=roofline, int32_valu=alu, cpu_baseline=cpu,
+               end_to_end_ms=end_to_end,
+               end_to_end_tasksets_per_s=None if end_to_end is None else N / (end_to_end * 1e-3),
+               per_workload=per_workload)
     B.gcaps_destroy(ctx)
     print(json.dumps(out))
 
@@ -289,7 +389,7 @@ def bench_gprio(args, batch, N, cores, per_core, S):
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(16, os.cpu_count() or 1)
+        threads = host_threads()
         sample = min(N, 200_000)
         sub = {k: v[:sample] for k, v in batch.items()}
         skip = modes[head]["skip"]
@@ -466,7 +566,7 @@ def bench_stream(args):
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(16, os.cpu_count() or 1)
+        threads = host_threads()
         host = B.to_host(d)
         t0c = time.perf_counter()
         want_r, want_s, _ = oracle.rta_batch(host, oracle.POLICY_BOTH, wait, threads=threads)
@@ -549,7 +649,7 @@ def bench_sim(args):
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(16, os.cpu_count() or 1)
+        threads = host_threads()
         sample = min(N, 96)
         sub = {k: v[:sample] for k, v in batch.items()}
         t0 = time.perf_counter()
