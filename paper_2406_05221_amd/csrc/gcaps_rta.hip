@@ -23,6 +23,7 @@
 #include "rta_bin.hip.inc"
 #include "gprio_wide.hip.inc"
 #include "gprio_fast.hip.inc"
+#include "gprio_tile.hip.inc"
 #include "gprio_given.hip.inc"
 #include "sim.hip.inc"
 #include "taskgen_device.hip.inc"
@@ -136,6 +137,7 @@ struct gcaps_ctx {
                                every lane then takes many tasksets) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
   u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
+  bool gprio_list = false;  /* GCAPS_GPRIO_KERNEL=list: the priority search as two launches with a list between them */
   bool legacy_deep = false; /* GCAPS_DEEP_KERNEL=lds: the second launch in its LDS-record form for every shape */
   size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
   u32 ts_offset = 0;                        /* first taskset of the current chunk */
@@ -580,10 +582,36 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
   const u32 N = b->n_tasksets, n = b->n_tasks;
   u32 *status = status_of(ctx);
   /* the quad-lane kernel takes shapes up to 32 tasks; what it cannot represent in 24 bits it lists */
-  ctx->wide_only = n > 32 || gprio::gprio_lds_bytes(n) > (size_t)ctx->lds_limit;
+  ctx->wide_only = n > 32 || gprio::gprio_lds_bytes(n) > (size_t)ctx->lds_limit ||
+                   gprio::tile_lds_bytes(n, 16u) > (size_t)ctx->lds_limit;
   const u32 *d_list = nullptr, *d_count = nullptr;
   u32 items = N;
-  if (!ctx->wide_only) {
+  if (!ctx->wide_only && !ctx->gprio_list) {
+    /* one pass: a wavefront per tile of consecutive tasksets reads them once, settles or searches them, and
+     * writes their outputs */
+    int rc = ctx->pool.wide_list.reserve((size_t)N * sizeof(u32), !ctx->capturing);
+    if (rc != GCAPS_OK) return rc;
+    u32 *wl = (u32 *)ctx->pool.wide_list.ptr;
+    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+    /* sixteen tasksets per wavefront: wider tiles (32, 64) fill the quads of the search better but hold fewer
+     * wavefronts per compute unit, and measured slower on every workload */
+    constexpr u32 tw = 16;
+    const size_t lds = gprio::tile_lds_bytes(n, tw);
+    const dim3 grid((N + tw - 1u) / tw), block(64);
+#define GCAPS_GPRIO_TILE(BUSY, NS)                                                                       \
+  hipLaunchKernelGGL((gprio::gprio_tile_kernel<BUSY, NS, 16>), grid, block, lds, ctx->stream, *b, d_skip, \
+                     (int *)d_gprio, (long long *)d_resp, d_sched, status, wl, ctx->ts_offset)
+    if (n <= 20) {
+      if (busy) GCAPS_GPRIO_TILE(true, 5); else GCAPS_GPRIO_TILE(false, 5);
+    } else {
+      if (busy) GCAPS_GPRIO_TILE(true, 8); else GCAPS_GPRIO_TILE(false, 8);
+    }
+#undef GCAPS_GPRIO_TILE
+    if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
+    d_list = wl;
+    d_count = status + fast::ST_WIDE_COUNT;
+    items = N < 65536u ? N : 65536u;
+  } else if (!ctx->wide_only) {
     int rc = ctx->pool.wide_list.reserve((size_t)N * sizeof(u32), !ctx->capturing);
     /* tiles of the first launch go to the list regions round-robin: a region never overflows */
     const u32 producer_tiles = (N + 63u) / 64u;
@@ -593,12 +621,12 @@ int run_gprio_chunk(gcaps_ctx *ctx, const gcaps_batch *b, int wait_mode, const u
     const fast::ListSpec dl{(u32 *)ctx->pool.deep_list.ptr, status + fast::ST_DEEP_COUNTS, fast::kListRegions,
                             ctx->region_cap, nullptr, nullptr, nullptr};
     u32 *wl = (u32 *)ctx->pool.wide_list.ptr;
+    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
     /* first launch: every taskset; settles what needs no search and lists the rest */
     hipLaunchKernelGGL(gprio::gprio_screen_kernel, dim3(producer_tiles), dim3(64), 0, ctx->stream, *b, d_skip,
                        (int *)d_gprio, (long long *)d_resp, d_sched, status, wl, dl, ctx->ts_offset);
     if (hipGetLastError() != hipSuccess) return GCAPS_EDEVICE;
-    /* second launch: the search, persistent workgroups over the list */
-    const bool busy = wait_mode == GCAPS_WAIT_BUSY;
+    /* second launch: the listed searches, sixteen per wavefront, persistent workgroups */
     const size_t lds = gprio::gprio_lds_bytes(n);
     const void *fn5 = busy ? (const void *)gprio::gprio_fast_kernel<true, 5>
                            : (const void *)gprio::gprio_fast_kernel<false, 5>;
@@ -838,6 +866,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
     if (v >= 1 && v <= 255) ctx->screen_tasks = (u32)v;
   }
   if (const char *e = getenv("GCAPS_DEEP_KERNEL")) ctx->legacy_deep = e[0] == 'l';
+  if (const char *e = getenv("GCAPS_GPRIO_KERNEL")) ctx->gprio_list = e[0] == 'l';
   if (const char *e = getenv("GCAPS_DEEP_LANES")) {
     const long v = strtol(e, nullptr, 10);
     if (v == 4 || v == 8) ctx->deep_lanes = (u32)v;

@@ -66,6 +66,23 @@ def test_mostly_schedulable_tasksets(oracle, gpu):
         assert 0.1 * 2 * 5_003 < found < 0.99 * 2 * 5_003
 
 
+def test_two_launch_route_of_the_search(oracle, monkeypatch):
+    """GCAPS_GPRIO_KERNEL=list: the first launch only settles and lists, the second searches sixteen listed
+    tasksets per wavefront (the faster route when most tasksets are searched deeply); same results."""
+    import torch
+    from paper_2406_05221_amd import binding as B, taskgen
+    monkeypatch.setenv("GCAPS_GPRIO_KERNEL", "list")
+    ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
+    try:
+        for batch in (taskgen.config(3, 6_000), relaxed_workload(4_001, seed=8), few_gpu_tasks_workload(1_037, seed=3),
+                      relaxed_workload(515, seed=9, n_cores=4, per_core=8, S=2)):
+            compare(oracle, B, ctx, batch)
+            _, sched = B.gcaps_rta_batch(ctx, batch, GCAPS, BUSY)
+            compare(oracle, B, ctx, batch, skip=sched[0], waits=(BUSY,))
+    finally:
+        B.gcaps_destroy(ctx)
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 0), (1, 1, 1), (2, 1, 2), (3, 7, 1), (8, 4, 5), (4, 8, 2), (5, 13, 2),
                                    (2, 3, 11), (2, 17, 4), (16, 2, 3)])
 def test_shapes_and_ragged_batches(oracle, gpu, shape):
