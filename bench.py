@@ -28,24 +28,29 @@ HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3), multiply-add, compare
 
-# VALU work of one step as the hardware counted it (SQ_INSTS_VALU summed over the launches of a step, and the
-# active-lane share SQ_THREAD_CYCLES_VALU / (64 x SQ_ACTIVE_INST_VALU... see the profile files), per workload,
-# 1,000,000 tasksets, mean of the two waiting modes; valid for the kernel sources they were taken with
-# (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
-MEASURED_VALU = dict(csrc_sha256="", per_workload={})
+# VALU work of one step as the hardware counted it, summed over the launches of a step: wavefront
+# instructions (SQ_INSTS_VALU) and lane-operations (SQ_THREAD_CYCLES_VALU: one per active lane and
+# instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
+# taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
+MEASURED_VALU = dict(
+    csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134", tasksets=1_000_000,
+    per_workload={"3": dict(busy=dict(valu_wave_insts=59_960_848, valu_lane_ops=2_828_336_537),
+                            suspend=dict(valu_wave_insts=65_899_958, valu_lane_ops=2_988_116_204)),
+                  "0": dict(busy=dict(valu_wave_insts=388_398_228, valu_lane_ops=22_626_980_511),
+                            suspend=dict(valu_wave_insts=591_965_879, valu_lane_ops=34_546_042_864))})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="2e6b09f412999c309fff2a85b006cd52d6f6eab17efb18d5757ac9f32a405f23",
-                        workload=3, tasksets=1_000_000, fetch_bytes=943826534, write_bytes=333292339)
+MEASURED_TRAFFIC = dict(csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134",
+                        workload=3, tasksets=1_000_000, fetch_bytes=947059200, write_bytes=340287232)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="2e6b09f412999c309fff2a85b006cd52d6f6eab17efb18d5757ac9f32a405f23",
-                              workload=3, tasksets=1_000_000, fetch_bytes=1235789926, write_bytes=251419494)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134",
+                              workload=3, tasksets=1_000_000, fetch_bytes=864285491, write_bytes=242001818)
 
 
 def csrc_sha256():
@@ -154,6 +159,7 @@ def main():
                          "schedulable under GCAPS), not a headline")
     ap.add_argument("--tasksets", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the VALU rate probe (keeps a kernel trace short)")
     ap.add_argument("--no-end-to-end", action="store_true", help="skip the timing of the host entry point")
     ap.add_argument("--no-per-workload", action="store_true", help="skip the device timings of the other workloads")
     ap.add_argument("--binning", type=int, default=0, choices=[0, 1])
@@ -286,29 +292,34 @@ def main():
                     traffic=traffic, kernel="gcaps_rta_batch_device (all launches of one step)",
                     algorithmic_bytes_per_taskset=algorithmic_bytes_per_taskset(n, S, P))
     # the arithmetic side: the probe's rates are measured now, on this device
-    rates = B.gcaps_valu_probe(ctx)
-    term_mix = rates["lane_ops_per_s"]["term"]
     alu = dict(peak=VALU_PEAK_LANE_OPS, peak_by="256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz",
-               probe_lane_ops_per_s=rates["lane_ops_per_s"], probe_clock_khz=rates["clock_khz"],
-               probe_cu_count=rates["cu_count"],
-               peak_measured_term_mix=term_mix,
                note="6 integer ops per interference term evaluated by plain iteration (oracle count); "
                     "peak_measured_term_mix = the add, 24-bit multiply-high, shift, 24-bit multiply-add of one term "
                     "in independent chains, measured in this run")
+    term_mix = None
+    if not args.no_probe:
+        rates = B.gcaps_valu_probe(ctx)
+        term_mix = rates["lane_ops_per_s"]["term"]
+        alu.update(probe_lane_ops_per_s=rates["lane_ops_per_s"], probe_clock_khz=rates["clock_khz"],
+                   probe_cu_count=rates["cu_count"], peak_measured_term_mix=term_mix)
     if terms_per_taskset is not None:
         ops = OPS_PER_TERM * terms_per_taskset * N / (m["device_ms_per_step"] * 1e-3)
         alu.update(terms_per_taskset=terms_per_taskset, terms_per_s=ops / OPS_PER_TERM, int32_lane_ops_per_s=ops,
-                   frac=ops / VALU_PEAK_LANE_OPS, frac_of_measured_term_mix=ops / term_mix)
+                   frac=ops / VALU_PEAK_LANE_OPS,
+                   frac_of_measured_term_mix=None if term_mix is None else ops / term_mix)
     mv = MEASURED_VALU
-    counted = mv["per_workload"].get(str(args.workload))
+    counted = mv["per_workload"].get(str(args.workload), {}).get(head)
     alu["measured_valu_lane_ops_per_s"] = None
-    if (counted and N == counted["tasksets"] and not args.binning and not args.continue_after_miss
+    if (counted and N == mv["tasksets"] and not args.binning and not args.continue_after_miss
             and mv["csrc_sha256"] == csrc_sha256()):
-        lane_ops = counted["valu_wave_insts"] * counted["active_lanes"]
-        alu.update(measured_valu_lane_ops_per_s=lane_ops / (m["device_ms_per_step"] * 1e-3),
+        rate = counted["valu_lane_ops"] / (m["device_ms_per_step"] * 1e-3)
+        alu.update(measured_valu_lane_ops_per_s=rate, measured_frac=rate / VALU_PEAK_LANE_OPS,
                    measured_valu_wave_insts_per_step=counted["valu_wave_insts"],
-                   measured_active_lanes_per_valu_inst=counted["active_lanes"],
-                   measured_frac=lane_ops / (m["device_ms_per_step"] * 1e-3) / VALU_PEAK_LANE_OPS)
+                   measured_active_lanes_per_valu_inst=counted["valu_lane_ops"] / counted["valu_wave_insts"],
+                   measured_valu_issue_frac=counted["valu_wave_insts"] * 4 / (256 * 4 * 2.4e9 * m["device_ms_per_step"] * 1e-3),
+                   measured_note="hardware counters of an earlier run of these kernel sources over the time of "
+                                 "this run; issue fraction = VALU wavefront-instructions x 4 cycles over the "
+                                 "SIMD-cycles of the step")
 
     # the host entry point: pack, copy in, analyse, copy out (the PCIe-inclusive rate; never `value`)
     end_to_end = None

@@ -130,6 +130,11 @@ enum {
  *   GCAPS_SCREEN_TASKS    tasks per taskset that the first launch analyses (default 4)
  *   GCAPS_DEEP_LANES      lanes per taskset in the second launch, 4 (default) or 8
  *   GCAPS_CHUNK_TASKSETS  cap on the tasksets per internal chunk of a call
+ *   GCAPS_DEEP_KERNEL     "lds": the second launch of the analysis keeps its term records in LDS for every
+ *                         shape (default: in registers for shapes of at most 32 tasks)
+ *   GCAPS_GPRIO_KERNEL    "list": the priority search as two launches, the second packing sixteen searched
+ *                         tasksets per wavefront (faster when most tasksets are searched deeply; default: one
+ *                         pass in which a wavefront reads, searches and answers 16 consecutive tasksets)
  */
 int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream);
 
