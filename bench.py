@@ -33,7 +33,7 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
 # taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
 MEASURED_VALU = dict(
-    csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134", tasksets=1_000_000,
+    csrc_sha256="bbb6f80dd901b775559c936901bda91c383b3689b3e6379adc86c1fb3b0bc828", tasksets=1_000_000,
     per_workload={"3": dict(busy=dict(valu_wave_insts=59_960_848, valu_lane_ops=2_828_336_537),
                             suspend=dict(valu_wave_insts=65_899_958, valu_lane_ops=2_988_116_204)),
                   "0": dict(busy=dict(valu_wave_insts=388_398_228, valu_lane_ops=22_626_980_511),
@@ -42,25 +42,31 @@ MEASURED_VALU = dict(
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
-# Valid only for the kernel sources the counters were taken with.
-MEASURED_TRAFFIC = dict(csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134",
+# Valid only for the kernel sources the counters were taken with (RTA_SOURCES / GPRIO_SOURCES below).
+MEASURED_TRAFFIC = dict(csrc_sha256="bbb6f80dd901b775559c936901bda91c383b3689b3e6379adc86c1fb3b0bc828",
                         workload=3, tasksets=1_000_000, fetch_bytes=947059200, write_bytes=340287232)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="7fcf60ba8fe17c6dadd4a35df0f05aedd911f19a0179a80225704bfe0c9b0134",
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="97f00a1400fc6cfc96e61e5331738ddfdc71d389783253339b2c2178ac34da6c",
                               workload=3, tasksets=1_000_000, fetch_bytes=864285491, write_bytes=242001818)
 
 
-def csrc_sha256():
+# the sources a row's kernels are built from: its counters stay valid while these are unchanged
+RTA_SOURCES = ("gcaps_rta.hip", "rta_fast.hip.inc", "rta_quad.hip.inc", "rta_deep.hip.inc", "rta_wide.hip.inc",
+               "rta_bin.hip.inc")
+GPRIO_SOURCES = ("gcaps_rta.hip", "rta_fast.hip.inc", "rta_wide.hip.inc", "gprio_tile.hip.inc", "gprio_fast.hip.inc",
+                 "gprio_wide.hip.inc")
+
+
+def csrc_sha256(names=RTA_SOURCES):
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2406_05221_amd", "csrc")
-    for name in sorted(os.listdir(d)):
-        if name.endswith((".hip", ".inc", ".h")):
-            h.update(name.encode())
-            h.update(open(os.path.join(d, name), "rb").read())
+    for name in sorted(names):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
     return h.hexdigest()
 
 
@@ -185,7 +191,8 @@ def main():
                     help="--row rta: analyse every task, with D_h for the unknown R_h below a miss (not the headline)")
     args = ap.parse_args()
     if args.print_csrc_hash:
-        print(csrc_sha256())
+        print("rta", csrc_sha256(RTA_SOURCES))
+        print("gprio", csrc_sha256(GPRIO_SOURCES))
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is built and measured on ONE GPU; run it with --gpus 1 "
@@ -430,7 +437,7 @@ def bench_gprio(args, batch, N, cores, per_core, S):
     traffic = None
     mt = MEASURED_TRAFFIC_GPRIO
     if (mt["csrc_sha256"] and args.workload == mt["workload"] and N == mt["tasksets"] and not args.search_all
-            and mt["csrc_sha256"] == csrc_sha256()):
+            and mt["csrc_sha256"] == csrc_sha256(GPRIO_SOURCES)):
         traffic = mt["fetch_bytes"] + mt["write_bytes"]
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
                     traffic=traffic, kernel="gcaps_gprio_assign_batch_device (all launches of one step)",

@@ -52,7 +52,7 @@ struct Rng {
  * log2(x) for a finite x > 0 and 2^x for |x| < 1000, to about 1e-13: enough for drawing periods
  * and utilisations, and the same bits wherever IEEE double arithmetic is.
  *   x = m 2^e, m in (sqrt(1/2), sqrt(2)]:  log2 x = e + (2/ln 2) t (1 + t^2/3 + ... + t^14/15), t = (m-1)/(m+1)
- *   x = i + f, f in [0,1):                 2^x = 2^i (1 + z (1 + z/2 (1 + ... z/14))), z = f ln 2
+ *   x = i + f, f in [0,1):                 2^x = 2^i sum_{k <= 14} z^k / k!, z = f ln 2 (Horner's rule)
  */
 double gen_log2(double x) {
   uint64_t bits;
@@ -81,8 +81,22 @@ double gen_log2(double x) {
 double gen_exp2(double x) {
   const double fl = std::floor(x);
   const double z = (x - fl) * 0.6931471805599453;
-  double p = 1.0;
-  for (int k = 14; k >= 1; --k) p = 1.0 + (z * p) / (double)k;
+  /* sum_{k <= 14} z^k / k! by Horner's rule; the constants are 1/k! rounded to double */
+  double p = 1.1470745597729725e-11;
+  p = p * z + 1.6059043836821613e-10;
+  p = p * z + 2.08767569878681e-09;
+  p = p * z + 2.505210838544172e-08;
+  p = p * z + 2.755731922398589e-07;
+  p = p * z + 2.7557319223985893e-06;
+  p = p * z + 2.48015873015873e-05;
+  p = p * z + 0.0001984126984126984;
+  p = p * z + 0.001388888888888889;
+  p = p * z + 0.008333333333333333;
+  p = p * z + 0.041666666666666664;
+  p = p * z + 0.16666666666666666;
+  p = p * z + 0.5;
+  p = p * z + 1.0;
+  p = p * z + 1.0;
   uint64_t bits;
   __builtin_memcpy(&bits, &p, sizeof bits); /* p in [1, 2]: scaling by 2^i is an add to the exponent */
   bits += (uint64_t)((int64_t)fl) << 52;
