@@ -132,6 +132,7 @@ enum {
  *   GCAPS_CHUNK_TASKSETS  cap on the tasksets per internal chunk of a call
  *   GCAPS_DEEP_KERNEL     "lds": the second launch of the analysis keeps its term records in LDS for every
  *                         shape (default: in registers for shapes of at most 32 tasks)
+ *   GCAPS_GEN_KERNEL      "taskset": gcaps_taskgen_device with one lane per taskset (default: one lane per task)
  *   GCAPS_GPRIO_KERNEL    "list": the priority search as two launches, the second packing sixteen searched
  *                         tasksets per wavefront (faster when most tasksets are searched deeply; default: one
  *                         pass in which a wavefront reads, searches and answers 16 consecutive tasksets)

@@ -137,6 +137,7 @@ struct gcaps_ctx {
                                every lane then takes many tasksets) */
   u32 screen_tasks = 4;     /* tasks per taskset analysed by the first fast launch (GCAPS_SCREEN_TASKS) */
   u32 deep_lanes = 4;       /* lanes per taskset in the second fast launch, 4 or 8 (GCAPS_DEEP_LANES) */
+  bool gen_by_taskset = false; /* GCAPS_GEN_KERNEL=taskset: the generator with one lane per taskset */
   bool gprio_list = false;  /* GCAPS_GPRIO_KERNEL=list: the priority search as two launches with a list between them */
   bool legacy_deep = false; /* GCAPS_DEEP_KERNEL=lds: the second launch in its LDS-record form for every shape */
   size_t resp_stride = 0, sched_stride = 0; /* elements between the policies of the current call */
@@ -867,6 +868,7 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
   }
   if (const char *e = getenv("GCAPS_DEEP_KERNEL")) ctx->legacy_deep = e[0] == 'l';
   if (const char *e = getenv("GCAPS_GPRIO_KERNEL")) ctx->gprio_list = e[0] == 'l';
+  if (const char *e = getenv("GCAPS_GEN_KERNEL")) ctx->gen_by_taskset = e[0] == 't';
   if (const char *e = getenv("GCAPS_DEEP_LANES")) {
     const long v = strtol(e, nullptr, 10);
     if (v == 4 || v == 8) ctx->deep_lanes = (u32)v;
@@ -1213,7 +1215,14 @@ extern "C" int gcaps_taskgen_device(gcaps_ctx *ctx, const gcaps_taskgen_spec *sp
     return GCAPS_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return GCAPS_EDEVICE;
-  /* stores gathered through LDS where a taskset's per-task values fit; else the plain kernel */
+  /* one lane per task where three words per task of 16 tasksets fit LDS and element indices fit 32 bits */
+  if (!ctx->gen_by_taskset && gen::element_lds_bytes(b->n_tasks) <= (size_t)ctx->lds_limit &&
+      (uint64_t)b->n_tasksets * b->n_tasks * (b->max_gseg ? b->max_gseg : 1u) < (1ull << 32)) {
+    hipLaunchKernelGGL(gen::generate_element_kernel, dim3((b->n_tasksets + 15u) / 16u), dim3(64),
+                       gen::element_lds_bytes(b->n_tasks), ctx->stream, *b, *sp);
+    return hipGetLastError() == hipSuccess ? GCAPS_OK : GCAPS_EDEVICE;
+  }
+  /* one lane per taskset: stores gathered through LDS where a taskset's per-task values fit; else the plain kernel */
   const u32 S = b->max_gseg;
   u32 tb = S ? 16u / S : 1u;
   if (tb < 1u) tb = 1u;

@@ -72,8 +72,8 @@ def test_regenerated_in_pieces_and_analysed_where_it_is(oracle, gpu):
 
 
 def test_relaxed_recipes_and_cpu_only_tasks_match_too(oracle, gpu):
-    """Ranges other than the named workloads', CPU-only tasks (eta = 0: the whole demand stays CPU time) and a
-    shape whose values do not fit LDS (80 tasks: the kernel that stores word by word)."""
+    """Ranges other than the named workloads', CPU-only tasks (eta = 0: the whole demand stays CPU time), 80 tasks,
+    one core, a period range of two values (ties in the rate-monotonic order)."""
     import torch
     from paper_2406_05221_amd import taskgen
     B, ctx, stream = gpu
@@ -92,6 +92,31 @@ def test_relaxed_recipes_and_cpu_only_tasks_match_too(oracle, gpu):
     # CPU-only tasks keep their whole demand: the utilisation per core is what was asked for
     cpu_only = host["n_gseg"] == 0
     assert (host["gm_us"].sum(2)[cpu_only] == 0).all()
+
+
+def test_one_lane_per_taskset_kernels_give_the_same_batches(monkeypatch):
+    """GCAPS_GEN_KERNEL=taskset: the generator kernels with one lane per taskset (stores gathered through LDS, or
+    word by word where a taskset's values do not fit), which serve shapes the one-lane-per-task kernel has no LDS for."""
+    import torch
+    from paper_2406_05221_amd import binding as B, taskgen
+    monkeypatch.setenv("GCAPS_GEN_KERNEL", "taskset")
+    stream = torch.cuda.Stream()
+    ctx = B.gcaps_create(0, stream.cuda_stream)
+    try:
+        cases = [taskgen.config_params(k, N, first_index=first)[1] | dict(N=N)
+                 for k, N, first in ((2, 9000, 0), (3, 50_000, 300_000), (4, 5_000, 7), (5, 21_600, 1_000_000))]
+        cases.append(dict(N=3_001, n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.25, 0.85), eta=(0, 3), share=(0.05, 0.5),
+                          period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024, seed=3, stream=1000))
+        for kw in cases:
+            N = kw.pop("N")
+            with torch.cuda.stream(stream):
+                d = B.gcaps_taskgen_device(ctx, N, **kw)
+            stream.synchronize()
+            dev, host = B.to_host(d), taskgen.generate(N, **kw)
+            for name in dev:
+                assert np.array_equal(dev[name], host[name]), (name, kw["n_cores"])
+    finally:
+        B.gcaps_destroy(ctx)
 
 
 def test_invalid_arguments(gpu):
