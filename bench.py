@@ -33,24 +33,24 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
 # taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
 MEASURED_VALU = dict(
-    csrc_sha256="8bd16b44d14257a137fe566151d0fc18728d5afaa39f0555f635f0fe07073158", tasksets=1_000_000,
-    per_workload={"3": dict(busy=dict(valu_wave_insts=59_974_549, valu_lane_ops=2_827_602_869),
-                            suspend=dict(valu_wave_insts=65_875_371, valu_lane_ops=2_985_562_380)),
-                  "0": dict(busy=dict(valu_wave_insts=388_396_915, valu_lane_ops=22_627_133_465),
-                            suspend=dict(valu_wave_insts=592_013_410, valu_lane_ops=34_547_968_670))})
+    csrc_sha256="c52e50e8e2b33e577d2a8f0dda9d913066777299157bcbf157ce19c11817a9a1", tasksets=1_000_000,
+    per_workload={"3": dict(busy=dict(valu_wave_insts=59_822_155, valu_lane_ops=2_786_127_848),
+                            suspend=dict(valu_wave_insts=65_721_677, valu_lane_ops=2_945_853_742)),
+                  "0": dict(busy=dict(valu_wave_insts=388_099_059, valu_lane_ops=22_612_216_635),
+                            suspend=dict(valu_wave_insts=591_805_080, valu_lane_ops=34_530_849_538))})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with (RTA_SOURCES / GPRIO_SOURCES below).
-MEASURED_TRAFFIC = dict(csrc_sha256="8bd16b44d14257a137fe566151d0fc18728d5afaa39f0555f635f0fe07073158",
-                        workload=3, tasksets=1_000_000, fetch_bytes=947156658, write_bytes=340292291)
+MEASURED_TRAFFIC = dict(csrc_sha256="c52e50e8e2b33e577d2a8f0dda9d913066777299157bcbf157ce19c11817a9a1",
+                        workload=3, tasksets=1_000_000, fetch_bytes=940929147, write_bytes=340286464)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="29ea89758bc8f53c456dac1f54701fbe69b2630df5da341491b66ab25033b6c3",
-                              workload=3, tasksets=1_000_000, fetch_bytes=864259774, write_bytes=242001792)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="ef368693335a205322cbf9468837334cbf084ac5e15a3b9af31b4c13b985286d",
+                              workload=3, tasksets=1_000_000, fetch_bytes=864258046, write_bytes=242001792)
 
 
 # the sources a row's kernels are built from: its counters stay valid while these are unchanged
