@@ -33,24 +33,24 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
 # taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
 MEASURED_VALU = dict(
-    csrc_sha256="c52e50e8e2b33e577d2a8f0dda9d913066777299157bcbf157ce19c11817a9a1", tasksets=1_000_000,
-    per_workload={"3": dict(busy=dict(valu_wave_insts=59_822_155, valu_lane_ops=2_786_127_848),
-                            suspend=dict(valu_wave_insts=65_721_677, valu_lane_ops=2_945_853_742)),
-                  "0": dict(busy=dict(valu_wave_insts=388_099_059, valu_lane_ops=22_612_216_635),
-                            suspend=dict(valu_wave_insts=591_805_080, valu_lane_ops=34_530_849_538))})
+    csrc_sha256="b5659f79ae92676c4e7ff154ab1eef235f4239aed40a702f1bb994173f70ac5b", tasksets=1_000_000,
+    per_workload={"3": dict(busy=dict(valu_wave_insts=59_845_351, valu_lane_ops=2_787_546_334),
+                            suspend=dict(valu_wave_insts=65_739_291, valu_lane_ops=2_946_947_411)),
+                  "0": dict(busy=dict(valu_wave_insts=388_099_078, valu_lane_ops=22_612_213_646),
+                            suspend=dict(valu_wave_insts=591_792_152, valu_lane_ops=34_530_112_734))})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with (RTA_SOURCES / GPRIO_SOURCES below).
-MEASURED_TRAFFIC = dict(csrc_sha256="c52e50e8e2b33e577d2a8f0dda9d913066777299157bcbf157ce19c11817a9a1",
-                        workload=3, tasksets=1_000_000, fetch_bytes=940929147, write_bytes=340286464)
+MEASURED_TRAFFIC = dict(csrc_sha256="b5659f79ae92676c4e7ff154ab1eef235f4239aed40a702f1bb994173f70ac5b",
+                        workload=3, tasksets=1_000_000, fetch_bytes=918949136, write_bytes=340255507)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="ef368693335a205322cbf9468837334cbf084ac5e15a3b9af31b4c13b985286d",
-                              workload=3, tasksets=1_000_000, fetch_bytes=864258046, write_bytes=242001792)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="ddae31bdf699afda7e19ffd6bd178e6d169183843484d1b72ae3fdbc216d031c",
+                              workload=3, tasksets=1_000_000, fetch_bytes=877260139, write_bytes=242015328)
 
 
 # the sources a row's kernels are built from: its counters stay valid while these are unchanged
@@ -207,10 +207,14 @@ def main():
     if args.row == "peak":
         ctx = B.gcaps_create(0, torch.cuda.Stream().cuda_stream)
         rates = B.gcaps_valu_probe(ctx)
+        hbm = B.gcaps_hbm_probe(ctx, 1 << 30)
         B.gcaps_destroy(ctx)
         rates["relative_to_spec"] = {k: v / rates["spec_lane_ops_per_s"] for k, v in rates["lane_ops_per_s"].items()}
         print(json.dumps(dict(metric="32-bit integer VALU lane-operations/sec by instruction kind, 1 MI355X",
-                              unit="lane-ops/s", n_gpus=1, **rates)))
+                              unit="lane-ops/s", n_gpus=1, **rates,
+                              hbm_GBs={k: v / 1e9 for k, v in hbm.items()}, hbm_peak_GBs=HBM_PEAK_GBS,
+                              hbm_note="bytes read + written per second of plain streaming kernels over 1 GiB "
+                                       "buffers; _stream: with the non-temporal hint")))
         return
     if args.row == "sim":
         return bench_sim(args)
@@ -314,6 +318,9 @@ def main():
         alu.update(terms_per_taskset=terms_per_taskset, terms_per_s=ops / OPS_PER_TERM, int32_lane_ops_per_s=ops,
                    frac=ops / VALU_PEAK_LANE_OPS,
                    frac_of_measured_term_mix=None if term_mix is None else ops / term_mix)
+    hbm_measured = None
+    if not args.no_probe:
+        hbm_measured = {k: v / 1e9 for k, v in B.gcaps_hbm_probe(ctx, 1 << 30).items()}
     mv = MEASURED_VALU
     counted = mv["per_workload"].get(str(args.workload), {}).get(head)
     alu["measured_valu_lane_ops_per_s"] = None
@@ -350,6 +357,7 @@ def main():
                            tasksets=N, n_tasks=n, max_gseg=S, policy="gcaps+rr", wait_mode=head,
                            binning=args.binning, continue_after_miss=bool(args.continue_after_miss)),
                modes=modes, roofline=roofline, int32_valu=alu, cpu_baseline=cpu,
+               hbm_measured_GBs=hbm_measured,  # plain streaming kernels over 1 GiB, this run; beside roofline.peak
                end_to_end_ms=end_to_end,
                end_to_end_tasksets_per_s=None if end_to_end is None else N / (end_to_end * 1e-3),
                per_workload=per_workload)

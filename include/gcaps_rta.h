@@ -59,6 +59,7 @@
 #ifndef GCAPS_RTA_H
 #define GCAPS_RTA_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -453,6 +454,33 @@ typedef struct {
   double lane_ops_per_s[GCAPS_PROBE_KINDS];
 } gcaps_valu_rates;
 int gcaps_valu_probe(gcaps_ctx *ctx, gcaps_valu_rates *out);
+
+/*
+ * Measured HBM rates of the context's device: what the memory gives plain streaming kernels in practice, the
+ * figure beside the published peak in this library's benchmark (no passage of the paper).  For each kind a
+ * kernel that reads, writes or copies `bytes` bytes of device memory, 16 bytes per lane and access, is timed
+ * alone with events on the context's stream; the call waits for the stream, allocates 2 * bytes of device memory
+ * for its duration and frees it.  `_STREAM` kinds give their accesses the non-temporal hint that the analysis
+ * kernels give to data they touch once.
+ *   bytes            size of each buffer: a multiple of 16, at least 1 MiB; take it well above the 256 MB of the
+ *                    memory-side cache (1 GiB in the benchmark)
+ *   bytes_per_s[k]   bytes read plus bytes written per second of kind k (a copy moves 2 * bytes)
+ * Errors: GCAPS_EINVAL, GCAPS_ENOMEM, GCAPS_EDEVICE.
+ */
+enum {
+  GCAPS_HBM_COPY = 0,
+  GCAPS_HBM_COPY_STREAM = 1,
+  GCAPS_HBM_READ = 2,
+  GCAPS_HBM_READ_STREAM = 3,
+  GCAPS_HBM_WRITE = 4,
+  GCAPS_HBM_WRITE_STREAM = 5,
+  GCAPS_HBM_KINDS = 6
+};
+typedef struct {
+  size_t bytes;
+  double bytes_per_s[GCAPS_HBM_KINDS];
+} gcaps_hbm_rates;
+int gcaps_hbm_probe(gcaps_ctx *ctx, size_t bytes, gcaps_hbm_rates *out);
 
 /* Static description of an error code. */
 const char *gcaps_strerror(int code);

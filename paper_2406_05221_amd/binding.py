@@ -28,7 +28,7 @@ EXPORTS = ["gcaps_create", "gcaps_destroy", "gcaps_rta_batch", "gcaps_rta_batch_
            "gcaps_last_wide_count", "gcaps_set_binning", "gcaps_strerror", "gcaps_gprio_assign_batch",
            "gcaps_gprio_assign_batch_device", "gcaps_set_continue_after_miss", "gcaps_gprio_rta_batch",
            "gcaps_gprio_rta_batch_device", "gcaps_simulate_batch", "gcaps_simulate_batch_device",
-           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static", "gcaps_valu_probe",
+           "gcaps_last_sim_steps", "gcaps_taskgen_device", "gcaps_rta_batch_device_static", "gcaps_valu_probe", "gcaps_hbm_probe",
            "gcaps_table3_count_device", "gcaps_table3_generate_device"]
 
 _p, _u32, _int = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_int
@@ -81,6 +81,16 @@ class gcaps_valu_rates(ctypes.Structure):
 
 _lib.gcaps_valu_probe.restype = _int
 _lib.gcaps_valu_probe.argtypes = [_p, ctypes.POINTER(gcaps_valu_rates)]
+
+HBM_KINDS = ["copy", "copy_stream", "read", "read_stream", "write", "write_stream"]
+
+
+class gcaps_hbm_rates(ctypes.Structure):
+    _fields_ = [("bytes", ctypes.c_size_t), ("bytes_per_s", ctypes.c_double * len(HBM_KINDS))]
+
+
+_lib.gcaps_hbm_probe.restype = _int
+_lib.gcaps_hbm_probe.argtypes = [_p, ctypes.c_size_t, ctypes.POINTER(gcaps_hbm_rates)]
 
 _FIELDS = [("theta_us", np.uint32, 1), ("eps_us", np.uint32, 1), ("slice_us", np.uint32, 1),
            ("cpu_us", np.uint32, 2), ("period_us", np.uint32, 2), ("deadline_us", np.uint32, 2),
@@ -208,6 +218,16 @@ def gcaps_valu_probe(ctx):
     return dict(cu_count=r.cu_count, clock_khz=r.clock_khz, wavefront_size=r.wavefront_size,
                 simd_per_cu=r.simd_per_cu, spec_lane_ops_per_s=r.spec_lane_ops_per_s,
                 lane_ops_per_s={k: r.lane_ops_per_s[i] for i, k in enumerate(PROBE_KINDS)})
+
+
+def gcaps_hbm_probe(ctx, nbytes=1 << 30):
+    """Measured HBM rates of the device: dict of bytes moved per second by kind (copy, read, write; plain or
+    with the non-temporal hint) over buffers of ``nbytes``."""
+    r = gcaps_hbm_rates()
+    rc = _lib.gcaps_hbm_probe(ctx, nbytes, ctypes.byref(r))
+    if rc != GCAPS_OK:
+        raise GcapsError(rc)
+    return {k: r.bytes_per_s[i] for i, k in enumerate(HBM_KINDS)}
 
 
 def gcaps_status(ctx):

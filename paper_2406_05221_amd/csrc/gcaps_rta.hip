@@ -29,6 +29,7 @@
 #include "taskgen_device.hip.inc"
 #include "taskgen_table3.hip.inc"
 #include "valu_probe.hip.inc"
+#include "hbm_probe.hip.inc"
 
 namespace {
 
@@ -1333,6 +1334,53 @@ extern "C" int gcaps_valu_probe(gcaps_ctx *ctx, gcaps_valu_rates *out) {
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
+  sink.release();
+  if (!ok) {
+    (void)hipGetLastError();
+    return GCAPS_EDEVICE;
+  }
+  return GCAPS_OK;
+}
+
+extern "C" int gcaps_hbm_probe(gcaps_ctx *ctx, size_t bytes, gcaps_hbm_rates *out) {
+  if (!ctx || !out || bytes < (1u << 20) || bytes % 16 != 0) return GCAPS_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return GCAPS_EDEVICE;
+  DeviceBuffer src, dst, sink;
+  int rc = src.reserve(bytes);
+  if (rc == GCAPS_OK) rc = dst.reserve(bytes);
+  if (rc == GCAPS_OK) rc = sink.reserve(256);
+  if (rc != GCAPS_OK) {
+    src.release();
+    dst.release();
+    sink.release();
+    return rc;
+  }
+  out->bytes = bytes;
+  /* one workgroup per 16 KB of the buffer (the kernels stride by the grid where that exceeds 2^20 workgroups) */
+  const size_t per_block = (size_t)256 * hbm::kUnroll * 16;
+  const u32 blocks = (u32)std::min<size_t>((bytes + per_block - 1) / per_block, (size_t)1 << 20);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+  /* the source holds defined values before anything reads it */
+  ok = ok && hbm::launch_kind(GCAPS_HBM_WRITE, ctx->stream, blocks, nullptr, src.ptr, bytes, (u32 *)sink.ptr) == hipSuccess;
+  for (int kind = 0; kind < GCAPS_HBM_KINDS && ok; ++kind) {
+    double best_ms = 0.0;
+    for (int rep = 0; rep < 4 && ok; ++rep) { /* the first repetition warms up; the fastest of the rest counts */
+      ok = hipEventRecord(e0, ctx->stream) == hipSuccess &&
+           hbm::launch_kind(kind, ctx->stream, blocks, src.ptr, dst.ptr, bytes, (u32 *)sink.ptr) == hipSuccess &&
+           hipEventRecord(e1, ctx->stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+      float ms = 0.0f;
+      ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+      if (ok && rep > 0 && (best_ms == 0.0 || ms < best_ms)) best_ms = ms;
+    }
+    out->bytes_per_s[kind] = best_ms > 0.0 ? hbm::bytes_moved(kind, bytes) / (best_ms * 1e-3) : 0.0;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) ok = false;
+  src.release();
+  dst.release();
   sink.release();
   if (!ok) {
     (void)hipGetLastError();

@@ -504,3 +504,24 @@ def test_argument_and_allocation_failures_leave_the_context_usable(oracle, gpu):
     assert call(300, 20, 3) == B.GCAPS_OK
     want_r, want_s, _ = oracle.rta_batch(good, BOTH, BUSY)
     assert np.array_equal(resp, want_r) and np.array_equal(sched, want_s)
+
+
+def test_rate_probes_report_plausible_rates(gpu):
+    """The denominators the benchmark prints: integer VALU rates by instruction kind and HBM rates of plain
+    streaming kernels.  Loose physical limits only (a rate of zero means a launch failed); the context goes on
+    working afterwards, and arguments the probe cannot use are refused."""
+    import ctypes
+    B, ctx, _ = gpu
+    valu = B.gcaps_valu_probe(ctx)
+    assert valu["cu_count"] > 0 and valu["wavefront_size"] == 64
+    for kind, rate in valu["lane_ops_per_s"].items():
+        assert 0.2 * valu["spec_lane_ops_per_s"] < rate < 2.5 * valu["spec_lane_ops_per_s"], (kind, rate)
+    hbm = B.gcaps_hbm_probe(ctx, 1 << 28)
+    assert set(hbm) == set(B.HBM_KINDS)
+    for kind, rate in hbm.items():
+        assert 0.5e12 < rate < 30e12, (kind, rate)  # 256 MiB may sit in the memory-side cache: above the HBM peak
+    r = B.gcaps_hbm_rates()
+    assert B._lib.gcaps_hbm_probe(ctx, 1000, ctypes.byref(r)) == B.GCAPS_EINVAL
+    assert B._lib.gcaps_hbm_probe(ctx, (1 << 20) + 8, ctypes.byref(r)) == B.GCAPS_EINVAL
+    assert B._lib.gcaps_hbm_probe(ctx, 1 << 50, ctypes.byref(r)) == B.GCAPS_ENOMEM
+    B.gcaps_status(ctx)
