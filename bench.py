@@ -485,7 +485,6 @@ def bench_stream_table3(args):
             M = int(idx.numel())
             outs[n] = (torch.empty((2, M, n), dtype=torch.int64, device="cuda:0"),
                        torch.empty((2, M), dtype=torch.uint8, device="cuda:0"))
-        torch.cuda.synchronize()
         for n, (idx, d) in groups.items():
             B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, *outs[n])
         B.gcaps_status(ctx)

@@ -498,8 +498,8 @@ def gcaps_table3_device(ctx, n_tasksets, *, seed=0, stream=300, first_index=0, d
     of ``taskgen.TABLE3`` can be overridden by keyword; best-effort tasks are not generated here).  Returns
     {n: (indices, batch)} like ``taskgen.table3``: one device batch per task count n, `indices` (int64 device
     tensor) saying which tasksets of the stream its rows are.  The tasksets are the host generator's, bit for bit.
-    Tensor bookkeeping (grouping by count) is done with torch on the device; one small copy of the distinct counts
-    comes back to the host."""
+    Tensor bookkeeping (grouping by count: one stable sort, one allocation per field shared by the groups) is done
+    with torch on the device; one small copy of the group sizes comes back to the host."""
     import torch
     from . import taskgen
     q = dict(taskgen.TABLE3)
@@ -523,23 +523,42 @@ def gcaps_table3_device(ctx, n_tasksets, *, seed=0, stream=300, first_index=0, d
     if rc != GCAPS_OK:
         raise GcapsError(rc)
     gcaps_status(ctx)  # waits for the context's stream
-    groups = {}
+    # one stable sort puts the tasksets of a count side by side, in stream order; one copy brings the sizes back
+    order = torch.argsort(count, stable=True)
+    order32 = order.to(torch.int32)
+    sizes = torch.bincount(count).tolist()
+    present = [(n, M) for n, M in enumerate(sizes) if M > 0]
+    # every field of every group in one allocation per field, each group's part at a multiple of 256 bytes
     kinds = {np.uint32: torch.int32, np.int32: torch.int32, np.uint8: torch.uint8}  # uint32 bits in int32 tensors
-    for n in torch.unique(count).tolist():
-        idx = torch.nonzero(count == n).flatten()
-        M = int(idx.numel())
-        idx32 = idx.to(torch.int32).contiguous()
+    per_row = {1: lambda n: 1, 2: lambda n: n, 3: lambda n: n * S}
+
+    def carve(dtype, ndim):
+        step = 256 // torch.empty(0, dtype=dtype).element_size()
+        starts, total = [], 0
+        for n, M in present:
+            starts.append(total)
+            total += -(-(M * per_row[ndim](n)) // step) * step
+        return torch.empty(total, dtype=dtype, device=device), starts
+
+    flat = {name: carve(kinds[dtype], ndim) for name, dtype, ndim in _FIELDS}
+    torch.cuda.current_stream().synchronize()  # the index lists were made on torch's stream
+    groups, first = {}, 0
+    for g, (n, M) in enumerate(present):
         shapes = {1: (M,), 2: (M, n), 3: (M, n, S)}
-        batch = {name: torch.empty(shapes[ndim], dtype=kinds[dtype], device=device) for name, dtype, ndim in _FIELDS}
+        batch = {}
+        for name, _, ndim in _FIELDS:
+            buf, starts = flat[name]
+            batch[name] = buf[starts[g]:starts[g] + M * per_row[ndim](n)].view(shapes[ndim])
         b = gcaps_batch(n_tasksets=M, n_tasks=n, max_gseg=S)
         for name, _, _ in _FIELDS:
             setattr(b, name, batch[name].data_ptr() if batch[name].numel() else None)
-        torch.cuda.current_stream().synchronize()  # idx32 was made on torch's stream
-        rc = _lib.gcaps_table3_generate_device(ctx, ctypes.byref(spec), idx32.data_ptr(), ctypes.byref(b))
+        rc = _lib.gcaps_table3_generate_device(ctx, ctypes.byref(spec), order32[first:first + M].data_ptr(),
+                                               ctypes.byref(b))
         if rc != GCAPS_OK:
             raise GcapsError(rc)
-        gcaps_status(ctx)
-        groups[int(n)] = (idx, batch)
+        groups[int(n)] = (order[first:first + M], batch)
+        first += M
+    gcaps_status(ctx)  # waits for the stream: the groups are written (their index lists come from the counts above)
     return groups
 
 
