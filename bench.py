@@ -33,24 +33,24 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
 # taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
 MEASURED_VALU = dict(
-    csrc_sha256="b5659f79ae92676c4e7ff154ab1eef235f4239aed40a702f1bb994173f70ac5b", tasksets=1_000_000,
-    per_workload={"3": dict(busy=dict(valu_wave_insts=59_845_351, valu_lane_ops=2_787_546_334),
-                            suspend=dict(valu_wave_insts=65_739_291, valu_lane_ops=2_946_947_411)),
-                  "0": dict(busy=dict(valu_wave_insts=388_099_078, valu_lane_ops=22_612_213_646),
-                            suspend=dict(valu_wave_insts=591_792_152, valu_lane_ops=34_530_112_734))})
+    csrc_sha256="4ebb276dc687ffac148777274a70ab4cdcfff7f2623c8dc6f990b2e9861e34c8", tasksets=1_000_000,
+    per_workload={"3": dict(busy=dict(valu_wave_insts=59_834_119, valu_lane_ops=2_786_869_606),
+                            suspend=dict(valu_wave_insts=65_726_872, valu_lane_ops=2_946_151_637)),
+                  "0": dict(busy=dict(valu_wave_insts=388_099_441, valu_lane_ops=22_612_234_571),
+                            suspend=dict(valu_wave_insts=591_803_684, valu_lane_ops=34_530_730_037))})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with (RTA_SOURCES / GPRIO_SOURCES below).
-MEASURED_TRAFFIC = dict(csrc_sha256="b5659f79ae92676c4e7ff154ab1eef235f4239aed40a702f1bb994173f70ac5b",
-                        workload=3, tasksets=1_000_000, fetch_bytes=918949136, write_bytes=340255507)
+MEASURED_TRAFFIC = dict(csrc_sha256="4ebb276dc687ffac148777274a70ab4cdcfff7f2623c8dc6f990b2e9861e34c8",
+                        workload=3, tasksets=1_000_000, fetch_bytes=918983896, write_bytes=340256757)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="ddae31bdf699afda7e19ffd6bd178e6d169183843484d1b72ae3fdbc216d031c",
-                              workload=3, tasksets=1_000_000, fetch_bytes=877260139, write_bytes=242015328)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="da508726e4c02b042d989791258b06e4c196468b2850bcfc10276114642591b3",
+                              workload=3, tasksets=1_000_000, fetch_bytes=877242676, write_bytes=242014883)
 
 
 # the sources a row's kernels are built from: its counters stay valid while these are unchanged

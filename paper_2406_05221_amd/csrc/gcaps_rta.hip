@@ -1357,7 +1357,7 @@ extern "C" int gcaps_hbm_probe(gcaps_ctx *ctx, size_t bytes, gcaps_hbm_rates *ou
     return rc;
   }
   out->bytes = bytes;
-  /* one workgroup per 16 KB of the buffer (the kernels stride by the grid where that exceeds 2^20 workgroups) */
+  /* one workgroup per 256 * kUnroll accesses (the kernels stride by the grid where that exceeds 2^20 workgroups) */
   const size_t per_block = (size_t)256 * hbm::kUnroll * 16;
   const u32 blocks = (u32)std::min<size_t>((bytes + per_block - 1) / per_block, (size_t)1 << 20);
   hipEvent_t e0 = nullptr, e1 = nullptr;
