@@ -73,7 +73,8 @@ def test_regenerated_in_pieces_and_analysed_where_it_is(oracle, gpu):
 
 def test_relaxed_recipes_and_cpu_only_tasks_match_too(oracle, gpu):
     """Ranges other than the named workloads', CPU-only tasks (eta = 0: the whole demand stays CPU time), 80 tasks,
-    one core, a period range of two values (ties in the rate-monotonic order)."""
+    one core, a period range of two values (ties in the rate-monotonic order), periods on both sides of 2^24 (the
+    generator ranks smaller ones by packed keys)."""
     import torch
     from paper_2406_05221_amd import taskgen
     B, ctx, stream = gpu
@@ -81,6 +82,8 @@ def test_relaxed_recipes_and_cpu_only_tasks_match_too(oracle, gpu):
                                 period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024, seed=3, stream=1000)),
                   (2_003, dict(n_cores=8, tasks_per_core=10, max_gseg=5, util=(0.1, 0.6), eta=(0, 5), share=(0.2, 0.7),
                                period=(500, 2_000_000), overhead=(300, 300), slice_us=2048, seed=4, stream=5)),
+                  (1_501, dict(n_cores=2, tasks_per_core=6, max_gseg=2, util=(0.2, 0.7), eta=(0, 2), share=(0.1, 0.6),
+                               period=(16_000_000, 40_000_000), overhead=(10, 20), slice_us=512, seed=6, stream=7)),
                   (777, dict(n_cores=1, tasks_per_core=9, max_gseg=1, util=(0.5, 0.99), eta=(1, 1), share=(0.1, 0.2),
                              period=(1_000, 1_001), overhead=(0, 0), slice_us=64, seed=5, stream=6))):
         with torch.cuda.stream(stream):
