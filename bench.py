@@ -33,24 +33,24 @@ OPS_PER_TERM = 6                           # add jitter, reciprocal ceil-div (~3
 # instruction), per workload and waiting mode, 1,000,000 tasksets; valid for the kernel sources they were
 # taken with (profiles/rta_step_workload3_counters.md, profiles/rta_step_workload0_counters.md).
 MEASURED_VALU = dict(
-    csrc_sha256="4ebb276dc687ffac148777274a70ab4cdcfff7f2623c8dc6f990b2e9861e34c8", tasksets=1_000_000,
-    per_workload={"3": dict(busy=dict(valu_wave_insts=59_834_119, valu_lane_ops=2_786_869_606),
-                            suspend=dict(valu_wave_insts=65_726_872, valu_lane_ops=2_946_151_637)),
-                  "0": dict(busy=dict(valu_wave_insts=388_099_441, valu_lane_ops=22_612_234_571),
-                            suspend=dict(valu_wave_insts=591_803_684, valu_lane_ops=34_530_730_037))})
+    csrc_sha256="14f51d6b715949ec02784f7f42a74b41aaae5b685fc8af4c819906c05c366888", tasksets=1_000_000,
+    per_workload={"3": dict(busy=dict(valu_wave_insts=59_609_954, valu_lane_ops=2_782_050_819),
+                            suspend=dict(valu_wave_insts=65_539_242, valu_lane_ops=2_941_143_253)),
+                  "0": dict(busy=dict(valu_wave_insts=386_276_643, valu_lane_ops=22_597_531_024),
+                            suspend=dict(valu_wave_insts=590_321_854, valu_lane_ops=34_526_990_874))})
 
 # HBM bytes of one default step (workload 3, both policies; mean of the two waiting modes), from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE summed over the launches of a step and scaled by what the same
 # counters read for a device-to-device copy of 1 GiB (profiles/rta_step_workload3_hbm_traffic.md).
 # Valid only for the kernel sources the counters were taken with (RTA_SOURCES / GPRIO_SOURCES below).
-MEASURED_TRAFFIC = dict(csrc_sha256="4ebb276dc687ffac148777274a70ab4cdcfff7f2623c8dc6f990b2e9861e34c8",
-                        workload=3, tasksets=1_000_000, fetch_bytes=918983896, write_bytes=340256757)
+MEASURED_TRAFFIC = dict(csrc_sha256="14f51d6b715949ec02784f7f42a74b41aaae5b685fc8af4c819906c05c366888",
+                        workload=3, tasksets=1_000_000, fetch_bytes=915827395, write_bytes=328834939)
 
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="da508726e4c02b042d989791258b06e4c196468b2850bcfc10276114642591b3",
-                              workload=3, tasksets=1_000_000, fetch_bytes=877242676, write_bytes=242014883)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="f6008f203682ac965652cf474f23ced70f588c47d2c4cfee61dd20cd74b413b1",
+                              workload=3, tasksets=1_000_000, fetch_bytes=877253532, write_bytes=242013979)
 
 
 # the sources a row's kernels are built from: its counters stay valid while these are unchanged

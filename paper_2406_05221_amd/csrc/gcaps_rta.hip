@@ -376,7 +376,8 @@ int launch_quad_any(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_m
   (busy ? launch_quad<true, NS, SEGS>(ctx, b, policy, d_resp, d_sched, kr, dl) \
         : launch_quad<false, NS, SEGS>(ctx, b, policy, d_resp, d_sched, kr, dl))
 #define GCAPS_QUAD(NS)                                                                           \
-  (b->max_gseg <= 4 ? GCAPS_QUAD_S(NS, 4)                                                        \
+  (b->max_gseg <= 3 ? GCAPS_QUAD_S(NS, 3)                                                        \
+   : b->max_gseg <= 4 ? GCAPS_QUAD_S(NS, 4)                                                      \
                     : b->max_gseg <= (u32)fast::kPrefetchSegs ? GCAPS_QUAD_S(NS, fast::kPrefetchSegs) \
                                                               : GCAPS_QUAD_S(NS, 0))
   if (b->n_tasks <= 20) return GCAPS_QUAD(5);
@@ -386,8 +387,8 @@ int launch_quad_any(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_m
 #undef GCAPS_QUAD_S
 }
 
-bool quad_applies(const gcaps_ctx *ctx, const gcaps_batch *b) {
-  return !ctx->cont && ctx->deep_lanes == 4 && b->n_tasks <= fast::kQuadMaxTasks && !ctx->legacy_deep;
+bool quad_applies(const gcaps_ctx *ctx, const gcaps_batch *b, u32 kr) {
+  return !ctx->cont && ctx->deep_lanes == 4 && b->n_tasks <= fast::kQuadMaxTasks && !ctx->legacy_deep && kr <= 4u;
 }
 
 template <bool CONT>
@@ -403,7 +404,7 @@ int launch_deep_c(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mod
 
 int launch_deep(gcaps_ctx *ctx, const gcaps_batch *b, int policy, int wait_mode, int64_t *d_resp,
                 uint8_t *d_sched, u32 kr) {
-  if (quad_applies(ctx, b))
+  if (quad_applies(ctx, b, kr))
     return launch_quad_any(ctx, b, policy, wait_mode, d_resp, d_sched, kr, deep_list_spec(ctx, ctx->binning != 0));
   return ctx->cont ? launch_deep_c<true>(ctx, b, policy, wait_mode, d_resp, d_sched, kr)
                    : launch_deep_c<false>(ctx, b, policy, wait_mode, d_resp, d_sched, kr);
@@ -920,7 +921,8 @@ extern "C" int gcaps_create(gcaps_ctx **out, int device_id, void *hip_stream) {
         (const void *)fast::rta_deep_kernel<true, 4, true>, (const void *)fast::rta_deep_kernel<false, 4, true>,
         (const void *)fast::rta_deep_kernel<true, 8, true>, (const void *)fast::rta_deep_kernel<false, 8, true>,
 #define GCAPS_QUAD_KERNELS(NS)                                                                                        \
-  (const void *)fast::rta_quad_kernel<true, NS, 4>, (const void *)fast::rta_quad_kernel<false, NS, 4>,                \
+  (const void *)fast::rta_quad_kernel<true, NS, 3>, (const void *)fast::rta_quad_kernel<false, NS, 3>,                \
+      (const void *)fast::rta_quad_kernel<true, NS, 4>, (const void *)fast::rta_quad_kernel<false, NS, 4>,            \
       (const void *)fast::rta_quad_kernel<true, NS, fast::kPrefetchSegs>,                                             \
       (const void *)fast::rta_quad_kernel<false, NS, fast::kPrefetchSegs>,                                            \
       (const void *)fast::rta_quad_kernel<true, NS, 0>, (const void *)fast::rta_quad_kernel<false, NS, 0>
