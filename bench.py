@@ -93,25 +93,37 @@ WORKLOAD0 = dict(n_cores=4, tasks_per_core=5, max_gseg=3, util=(0.25, 0.85), eta
                  period=(20_000, 1_000_000), overhead=(0, 40), slice_us=1024, seed=0, stream=1000)
 
 
-def timed_steps(B, ctx, stream, step, steps, warmup):
+def timed_steps(B, ctx, stream, step, steps, warmup, spread=True):
     """`warmup` untimed and `steps` timed calls of step() on the context's stream: (seconds of wall time over
-    the timed calls, device milliseconds of each from events on that stream)."""
+    the timed calls, device milliseconds per call from ONE pair of events around the timed calls on that stream,
+    device milliseconds of each call of a further, untimed round with an event pair per call).  Events between
+    the calls of the timed round would cost every step about 7 us of GPU idle time."""
     import torch
     for _ in range(warmup):
         step()
     B.gcaps_status(ctx)
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    first.record(stream)
     for k in range(steps):
-        starts[k].record(stream)
         step()
-        stops[k].record(stream)
+    last.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     B.gcaps_status(ctx)
-    return t1 - t0, [a.elapsed_time(b) for a, b in zip(starts, stops)]
+    each = []
+    if spread:
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        for k in range(steps):
+            starts[k].record(stream)
+            step()
+            stops[k].record(stream)
+        torch.cuda.synchronize()
+        B.gcaps_status(ctx)
+        each = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+    return t1 - t0, first.elapsed_time(last) / steps, each
 
 
 def other_workloads(B, taskgen, ctx, stream, steps, warmup, skip):
@@ -135,9 +147,9 @@ def other_workloads(B, taskgen, ctx, stream, steps, warmup, skip):
         torch.cuda.synchronize()
         row = dict(tasksets=N, n_tasks=n, max_gseg=params["max_gseg"])
         for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
-            _, dev = timed_steps(B, ctx, stream, lambda: B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait,
-                                                                                 resp, sched), steps, warmup)
-            row[f"device_ms_{name}"] = float(np.mean(dev))
+            _, dev, _ = timed_steps(B, ctx, stream, lambda: B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait,
+                                                                                    resp, sched), steps, warmup, spread=False)
+            row[f"device_ms_{name}"] = float(dev)
             row[f"sched_ratio_gcaps_{name}"] = float(sched[0].float().mean().item())
             row[f"tasksets_via_64bit_kernel_{name}"] = B.gcaps_last_wide_count(ctx)
         slow = max(row["device_ms_busy"], row["device_ms_suspend"])
@@ -245,12 +257,12 @@ def main():
 
     modes = {}
     for wait, name in ((B.GCAPS_WAIT_BUSY, "busy"), (B.GCAPS_WAIT_SUSPEND, "suspend")):
-        wall, dev_ms = timed_steps(B, ctx, stream,
-                                   lambda: B.gcaps_rta_batch_device(ctx, d, policy, wait, d_resp, d_sched),
-                                   args.steps, args.warmup)
+        wall, dev, dev_each = timed_steps(B, ctx, stream,
+                                          lambda: B.gcaps_rta_batch_device(ctx, d, policy, wait, d_resp, d_sched),
+                                          args.steps, args.warmup)
         modes[name] = dict(wall_ms_per_step=wall * 1e3 / args.steps,
-                           device_ms_per_step=float(np.mean(dev_ms)),
-                           device_ms_median=float(np.median(dev_ms)),
+                           device_ms_per_step=float(dev),  # one event pair around the timed calls
+                           device_ms_median=float(np.median(dev_each)),  # of a further round, one pair per call
                            tasksets_per_s=N * args.steps / wall,
                            sched_ratio_gcaps=float(d_sched[0].float().mean().item()),
                            sched_ratio_rr=float(d_sched[1].float().mean().item()),
@@ -388,26 +400,15 @@ def bench_gprio(args, batch, N, cores, per_core, S):
         B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_GCAPS, wait, d_r1, d_flags)
         B.gcaps_status(ctx)
         d_skip = None if args.search_all else d_flags[0].clone()
-        for _ in range(args.warmup):
-            B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio, d_resp, d_sched)
-        B.gcaps_status(ctx)
-        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            starts[k].record(stream)
-            B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio, d_resp, d_sched)
-            stops[k].record(stream)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        B.gcaps_status(ctx)
-        dev_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+        wall, dev, dev_each = timed_steps(B, ctx, stream,
+                                          lambda: B.gcaps_gprio_assign_batch_device(ctx, d, wait, d_skip, d_gprio,
+                                                                                    d_resp, d_sched),
+                                          args.steps, args.warmup)
         searched = N if d_skip is None else int(N - d_skip.sum().item())
         found = int(d_sched.sum().item()) - (N - searched)
-        modes[name] = dict(wall_ms_per_step=(t1 - t0) * 1e3 / args.steps, device_ms_per_step=float(np.mean(dev_ms)),
-                           device_ms_median=float(np.median(dev_ms)), tasksets_per_s=N * args.steps / (t1 - t0),
-                           searched=searched, searched_per_s=searched * args.steps / (t1 - t0),
+        modes[name] = dict(wall_ms_per_step=wall * 1e3 / args.steps, device_ms_per_step=float(dev),
+                           device_ms_median=float(np.median(dev_each)), tasksets_per_s=N * args.steps / wall,
+                           searched=searched, searched_per_s=searched * args.steps / wall,
                            assignments_found=found, tasksets_via_64bit_kernel=B.gcaps_last_wide_count(ctx),
                            skip=None if d_skip is None else d_skip.cpu().numpy())
     head = min(modes, key=lambda m: modes[m]["tasksets_per_s"])
@@ -575,19 +576,18 @@ def bench_stream(args):
             d = generate(specs[bidx], d)
             B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, d_resp, d_sched)
         B.gcaps_status(ctx)
-        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        first.record(stream)  # one event pair around the timed steps: events between them would idle the GPU
         for s in range(args.steps):
-            starts[s].record(stream)
             d = generate(specs[args.warmup + s], d)
             B.gcaps_rta_batch_device(ctx, d, B.GCAPS_POLICY_BOTH, wait, d_resp, d_sched)
-            stops[s].record(stream)
+        last.record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         B.gcaps_status(ctx)
-    dev_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, stops)]))
+    dev_ms = first.elapsed_time(last) / args.steps
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
