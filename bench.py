@@ -49,8 +49,8 @@ MEASURED_TRAFFIC = dict(csrc_sha256="14f51d6b715949ec02784f7f42a74b41aaae5b685fc
 
 # The same for `--row gprio` (workload 3; the skip flags of the run; mean of the two waiting modes;
 # profiles/gprio_step_workload3_hbm_traffic.md).
-MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="f6008f203682ac965652cf474f23ced70f588c47d2c4cfee61dd20cd74b413b1",
-                              workload=3, tasksets=1_000_000, fetch_bytes=877253532, write_bytes=242013979)
+MEASURED_TRAFFIC_GPRIO = dict(csrc_sha256="3d1f3d9819d9c94e3659b628b46be6cdc18f7517be3626a559ab12340c9b75d5",
+                              workload=3, tasksets=1_000_000, fetch_bytes=877660561, write_bytes=242013028)
 
 
 # the sources a row's kernels are built from: its counters stay valid while these are unchanged
