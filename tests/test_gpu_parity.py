@@ -295,6 +295,45 @@ def test_outputs_at_8_byte_alignment_only(oracle, gpu):
             assert (raw[:shift] == -7).all() and (raw[shift + 2 * N * n:] == -7).all()  # nothing outside the view
 
 
+def test_inputs_at_element_alignment_only(oracle, gpu):
+    """Every input array starts one element into a larger buffer: 4-byte aligned words, 1-byte aligned bytes.  The
+    kernels load several segment slots of a task with one instruction and stream arrays with wide accesses; none of
+    it may assume more than the element's own alignment.  Shapes with 1 to 5 segment slots, both entry points of the
+    analysis and the priority search."""
+    import torch
+    B, ctx, _ = gpu
+
+    def shifted(batch):
+        out = {}
+        for name, t in B.to_device(batch).items():
+            raw = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda:0")
+            raw[1:] = t.flatten()
+            out[name] = raw[1:].view(t.shape)
+            assert out[name].data_ptr() % 16 == t.element_size() and out[name].is_contiguous()
+        return out
+
+    for S in (1, 2, 3, 4, 5):
+        batch = relaxed_workload(1_037, seed=80 + S, n_cores=4, per_core=5, S=S)
+        N, n = batch["cpu_us"].shape
+        d = shifted(batch)
+        d_resp = torch.empty((2, N, n), dtype=torch.int64, device="cuda:0")
+        d_sched = torch.empty((2, N), dtype=torch.uint8, device="cuda:0")
+        for wait in (BUSY, SUSPEND):
+            torch.cuda.synchronize()
+            B.gcaps_rta_batch_device(ctx, d, BOTH, wait, d_resp, d_sched)
+            B.gcaps_status(ctx)
+            want_r, want_s, _ = oracle.rta_batch(batch, BOTH, wait, threads=16)
+            assert (d_resp.cpu().numpy() == want_r).all() and (d_sched.cpu().numpy() == want_s).all(), (S, wait)
+            d_gprio = torch.empty((N, n), dtype=torch.int32, device="cuda:0")
+            g_resp = torch.empty((N, n), dtype=torch.int64, device="cuda:0")
+            g_sched = torch.empty((N,), dtype=torch.uint8, device="cuda:0")
+            B.gcaps_gprio_assign_batch_device(ctx, d, wait, None, d_gprio, g_resp, g_sched)
+            B.gcaps_status(ctx)
+            wg, wr, ws, _ = oracle.gprio_assign_batch(batch, wait, threads=16)
+            assert (d_gprio.cpu().numpy() == wg).all() and (g_resp.cpu().numpy() == wr).all()
+            assert (g_sched.cpu().numpy() == ws).all(), (S, wait)
+
+
 def test_priorities_that_look_like_internal_marks(oracle, gpu):
     """Any int32 is a legal priority.  Values around 2^30 (the first launch marks looked-up tasks
     with such words in the priority column) and the extremes must not confuse anything."""
