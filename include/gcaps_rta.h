@@ -77,7 +77,9 @@ typedef struct gcaps_ctx gcaps_ctx; /* opaque: device id, stream, device scratch
  *
  * Layout: per-taskset arrays have n_tasksets elements; per-task arrays are
  * [n_tasksets][n_tasks] row-major, tasks in caller order (any priority order);
- * per-segment arrays are [n_tasksets][n_tasks][max_gseg] row-major.
+ * per-segment arrays are [n_tasksets][n_tasks][max_gseg] row-major.  Every array needs the alignment of its
+ * element type and no more (the outputs likewise: 8 bytes for the response times); arrays may be views into larger
+ * buffers.
  */
 typedef struct {
   uint32_t n_tasksets; /* >= 1 */
